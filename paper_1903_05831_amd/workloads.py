@@ -1,0 +1,187 @@
+"""Synthetic workloads: layer shapes of the five benchmark configurations and the
+seeded input generators that both the HIP path and the CPU checker are fed from.
+
+This module holds no convolution arithmetic.  Output extents are written out as
+literals in the tables (they are the shapes of a ResNet-50-C4 Faster R-CNN at
+800x1344 input, the detector the paper's Figure 1 is measured on); tests check that
+the library and the checker both derive the same extents from the descriptors.
+
+Value distributions: activations and upstream gradients ~ N(0,1); weights He-normal
+with variance 2/(R*S*C); all drawn in fp32 and rounded once to binary16 (RNE).
+"""
+from __future__ import annotations
+
+from dataclasses import dataclass
+from typing import Dict, List
+
+import numpy as np
+
+BASE_SEED = 190305831
+ROLE_X, ROLE_W, ROLE_G, ROLE_INF = 0, 1, 2, 3
+
+
+@dataclass(frozen=True)
+class ConvLayer:
+    name: str
+    N: int
+    H: int
+    W: int
+    C: int
+    K: int
+    R: int
+    S: int
+    stride: int
+    pad: int
+    Ho: int
+    Wo: int
+    dil: int = 1
+
+    @property
+    def x_shape(self):
+        return (self.N, self.H, self.W, self.C)
+
+    @property
+    def w_shape(self):
+        return (self.K, self.R, self.S, self.C)
+
+    @property
+    def y_shape(self):
+        return (self.N, self.Ho, self.Wo, self.K)
+
+    @property
+    def flops(self) -> int:
+        """Algorithmic FLOPs of ONE pass (2 per multiply-add, padding taps counted)."""
+        return 2 * self.N * self.Ho * self.Wo * self.K * self.R * self.S * self.C
+
+    @property
+    def dw_numel(self) -> int:
+        return self.K * self.R * self.S * self.C
+
+    def compulsory_bytes(self, pass_name: str) -> int:
+        """Bytes each tensor moves once: fp16 activations and weights, fp32 dw."""
+        xb = 2 * self.N * self.H * self.W * self.C
+        yb = 2 * self.N * self.Ho * self.Wo * self.K
+        wb = self.dw_numel
+        if pass_name == "wgrad":
+            return xb + yb + 4 * wb
+        return xb + yb + 2 * wb
+
+
+def _L(name, N, H, W, C, K, R, stride, pad, Ho, Wo):
+    return ConvLayer(name, N, H, W, C, K, R, R, stride, pad, Ho, Wo)
+
+
+def _res2_block(prefix, first: bool) -> List[ConvLayer]:
+    cin = 64 if first else 256
+    out = [_L(prefix + "a", 2, 200, 336, cin, 64, 1, 1, 0, 200, 336),
+           _L(prefix + "b", 2, 200, 336, 64, 64, 3, 1, 1, 200, 336),
+           _L(prefix + "c", 2, 200, 336, 64, 256, 1, 1, 0, 200, 336)]
+    if first:
+        out.append(_L(prefix + "p", 2, 200, 336, 64, 256, 1, 1, 0, 200, 336))
+    return out
+
+
+def _res3_block0() -> List[ConvLayer]:
+    return [_L("res3.0a", 2, 200, 336, 256, 128, 1, 1, 0, 200, 336),
+            _L("res3.0b", 2, 200, 336, 128, 128, 3, 2, 1, 100, 168),
+            _L("res3.0c", 2, 100, 168, 128, 512, 1, 1, 0, 100, 168),
+            _L("res3.0p", 2, 200, 336, 256, 512, 1, 2, 0, 100, 168)]
+
+
+def _res3_block(i) -> List[ConvLayer]:
+    p = f"res3.{i}"
+    return [_L(p + "a", 2, 100, 168, 512, 128, 1, 1, 0, 100, 168),
+            _L(p + "b", 2, 100, 168, 128, 128, 3, 1, 1, 100, 168),
+            _L(p + "c", 2, 100, 168, 128, 512, 1, 1, 0, 100, 168)]
+
+
+def _res4() -> List[ConvLayer]:
+    out = [_L("res4.0a", 2, 100, 168, 512, 256, 1, 1, 0, 100, 168),
+           _L("res4.0b", 2, 100, 168, 256, 256, 3, 2, 1, 50, 84),
+           _L("res4.0c", 2, 50, 84, 256, 1024, 1, 1, 0, 50, 84),
+           _L("res4.0p", 2, 100, 168, 512, 1024, 1, 2, 0, 50, 84)]
+    for i in range(1, 6):
+        p = f"res4.{i}"
+        out += [_L(p + "a", 2, 50, 84, 1024, 256, 1, 1, 0, 50, 84),
+                _L(p + "b", 2, 50, 84, 256, 256, 3, 1, 1, 50, 84),
+                _L(p + "c", 2, 50, 84, 256, 1024, 1, 1, 0, 50, 84)]
+    return out
+
+
+def _res5() -> List[ConvLayer]:
+    out = [_L("res5.0a", 512, 14, 14, 1024, 512, 1, 1, 0, 14, 14),
+           _L("res5.0b", 512, 14, 14, 512, 512, 3, 2, 1, 7, 7),
+           _L("res5.0c", 512, 7, 7, 512, 2048, 1, 1, 0, 7, 7),
+           _L("res5.0p", 512, 14, 14, 1024, 2048, 1, 2, 0, 7, 7)]
+    for i in range(1, 3):
+        p = f"res5.{i}"
+        out += [_L(p + "a", 512, 7, 7, 2048, 512, 1, 1, 0, 7, 7),
+                _L(p + "b", 512, 7, 7, 512, 512, 3, 1, 1, 7, 7),
+                _L(p + "c", 512, 7, 7, 512, 2048, 1, 1, 0, 7, 7)]
+    return out
+
+
+def _config5() -> List[ConvLayer]:
+    out = [_L("stem", 2, 800, 1344, 3, 64, 7, 2, 3, 400, 672)]
+    out += _res2_block("res2.0", True) + _res2_block("res2.1", False) + _res2_block("res2.2", False)
+    out += _res3_block0() + _res3_block(1) + _res3_block(2) + _res3_block(3)
+    out += _res4()
+    out += _res5()
+    return out
+
+
+CONFIGS: Dict[int, List[ConvLayer]] = {
+    1: [_L("conv3x3_64", 1, 56, 56, 64, 64, 3, 1, 1, 56, 56)],
+    2: _res2_block("res2.", False),
+    3: _res3_block0(),
+    4: _res4(),
+    5: _config5(),
+}
+
+CONFIG_NAMES = {
+    1: "single 3x3 64->64 conv at 56x56, N=1",
+    2: "ResNet-50 res2 bottleneck convs at 200x336, N=2",
+    3: "ResNet-50 res3 first block from 200x336x256, N=2",
+    4: "ResNet-50-C4 res4 trunk (6 bottlenecks) at 50x84, N=2",
+    5: "ResNet-50-C4 Faster R-CNN, all 53 convs, N=2 x 800x1344 + 512 RoIs",
+}
+
+
+def _rng(config_id: int, layer_index: int, role: int) -> np.random.Generator:
+    return np.random.default_rng(np.random.SeedSequence([BASE_SEED, config_id, layer_index, role]))
+
+
+def _normal_half(rng: np.random.Generator, shape, sigma: float) -> np.ndarray:
+    a = rng.standard_normal(size=shape, dtype=np.float32)
+    if sigma != 1.0:
+        a *= np.float32(sigma)
+    return a.astype(np.float16)
+
+
+def make_x(layer: ConvLayer, config_id: int, layer_index: int) -> np.ndarray:
+    return _normal_half(_rng(config_id, layer_index, ROLE_X), layer.x_shape, 1.0)
+
+
+def make_w(layer: ConvLayer, config_id: int, layer_index: int) -> np.ndarray:
+    sigma = float(np.sqrt(2.0 / (layer.R * layer.S * layer.C)))
+    return _normal_half(_rng(config_id, layer_index, ROLE_W), layer.w_shape, sigma)
+
+
+def make_g(layer: ConvLayer, config_id: int, layer_index: int) -> np.ndarray:
+    return _normal_half(_rng(config_id, layer_index, ROLE_G), layer.y_shape, 1.0)
+
+
+def inf_positions(n: int, config_id: int, fraction: float = 1e-4) -> np.ndarray:
+    """ceil(fraction*n) distinct flat indices at which a gradient buffer is set to +inf."""
+    count = int(np.ceil(fraction * n))
+    return np.sort(_rng(config_id, 0, ROLE_INF).choice(n, size=count, replace=False))
+
+
+def sample_indices(total: int, count: int, seed: int) -> np.ndarray:
+    """Seeded flat output indices for sampled parity checks (always holds first and last)."""
+    rng = np.random.default_rng(np.random.SeedSequence([BASE_SEED, 77, seed]))
+    count = min(count, total)
+    idx = rng.choice(total, size=count, replace=False) if count < total else np.arange(total)
+    idx[0] = 0
+    idx[-1] = total - 1
+    return np.unique(idx).astype(np.int64)
