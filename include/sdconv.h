@@ -1,0 +1,112 @@
+/*
+ * sdconv -- mixed-precision 2-D convolution for detector training on MI355X (gfx950).
+ *
+ * C ABI of the hot path behind the paper's mixed-precision training feature
+ * (section 2.2, "Mixed Precision Training": half-precision compute with the loss
+ * scaling of Micikevicius et al.; Figure 1(b) measures it on a Faster R-CNN with a
+ * ResNet-50-C4 backbone).  The library holds hand-written HIP kernels only; callers
+ * bring device memory and a HIP stream.
+ *
+ * Common conventions
+ *   - Every data pointer is a DEVICE pointer to a dense, contiguous tensor, aligned to
+ *     16 bytes, owned by the caller.  The library never allocates, frees or keeps device
+ *     memory.  Inputs and outputs must not overlap.
+ *   - Layouts (last index fastest):  x, dx [N][H][W][C]   y, dy [N][Ho][Wo][K]
+ *     w, dw [K][R][S][C].  x, w, y, dy, dx are IEEE binary16; dw is binary32.
+ *     Ho = floor((H + 2*pad_h - dil_h*(R-1) - 1) / stride_h) + 1, likewise Wo.
+ *   - Cross-correlation (no kernel flip), zero padding, groups = 1, no bias.
+ *   - Products are binary16 x binary16 accumulated in binary32 (MFMA); y and dx are
+ *     rounded once (nearest even) from the binary32 sum; dw stays binary32.
+ *   - `hip_stream` is a hipStream_t passed as void* (NULL = the default stream).  All
+ *     device work is enqueued on it and the call returns without waiting.
+ *   - `workspace` is caller-owned device scratch of at least conv2d_workspace_bytes()
+ *     bytes (may be NULL when that is 0), 256-byte aligned.  Its contents are undefined
+ *     after the call.  Calls that share a workspace must be ordered on one stream.
+ *   - Outputs are overwritten in full (beta = 0); dx positions that no filter tap
+ *     reaches are written as +0.
+ *   - Return value: SDCONV_OK or a negative SDCONV_E* code.  When an error is returned
+ *     nothing has been enqueued.  No exception crosses this boundary.
+ *   - Every tensor must hold fewer than 2^31 elements (kernels use 32-bit offsets).
+ *   - Thread safety: the library keeps no mutable global state except a per-thread
+ *     record of the last HIP error; calls from several host threads are safe.
+ */
+#ifndef SDCONV_H
+#define SDCONV_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct {
+    int32_t N, H, W, C;          /* input tensor, NHWC                       */
+    int32_t K, R, S;             /* filter bank KRSC, K = output channels    */
+    int32_t stride_h, stride_w;  /* >= 1                                     */
+    int32_t pad_h, pad_w;        /* >= 0, zeros on both sides                */
+    int32_t dil_h, dil_w;        /* >= 1                                     */
+} conv2d_desc;
+
+enum {
+    SDCONV_OK = 0,
+    SDCONV_EINVAL = -1,       /* null pointer, non-positive size, empty output, bad scale, misalignment */
+    SDCONV_EUNSUPPORTED = -2, /* reserved: every valid descriptor is supported                          */
+    SDCONV_EWORKSPACE = -3,   /* workspace missing or smaller than conv2d_workspace_bytes()             */
+    SDCONV_EHIP = -4          /* a HIP call failed; see sdconv_last_hip_error()                         */
+};
+
+enum { SDCONV_FWD = 0, SDCONV_DGRAD = 1, SDCONV_WGRAD = 2 };
+
+/* Output extent of the convolution `desc` describes.  Host-only, touches no device.
+ * Returns SDCONV_EINVAL for an invalid descriptor or an empty output. */
+int conv2d_out_shape(const conv2d_desc *desc, int32_t *Ho, int32_t *Wo);
+
+/* Device scratch the given pass needs for `desc` (0 for an invalid descriptor or pass).
+ * Host-only.  wgrad uses it for split-K partial sums, dgrad for a re-laid-out filter. */
+size_t conv2d_workspace_bytes(const conv2d_desc *desc, int pass);
+
+/* Forward: y[n,ho,wo,k] = sum_{r,s,c} x[n, ho*stride_h - pad_h + r*dil_h,
+ *                                         wo*stride_w - pad_w + s*dil_w, c] * w[k,r,s,c],
+ * reads outside the image are zero.  (Half-precision forward compute of section 2.2.) */
+int conv2d_fwd(const conv2d_desc *desc, const void *x, const void *w, void *y,
+               void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/* Data gradient (adjoint of conv2d_fwd in x):
+ * dx[n,h,w,c] = sum over (k,r,s) with ho*stride_h - pad_h + r*dil_h == h and
+ *               wo*stride_w - pad_w + s*dil_w == w of dy[n,ho,wo,k] * w[k,r,s,c].
+ * (Half-precision backward compute of section 2.2; dy carries the loss scale.) */
+int conv2d_dgrad(const conv2d_desc *desc, const void *dy, const void *w, void *dx,
+                 void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/* Weight gradient (adjoint of conv2d_fwd in w), binary32 result:
+ * dw[k,r,s,c] = sum_{n,ho,wo} dy[n,ho,wo,k] * x[n, ho*stride_h - pad_h + r*dil_h,
+ *                                                 wo*stride_w - pad_w + s*dil_w, c].
+ * The reduction over pixels is split across workgroups; partial sums are combined in a
+ * fixed order, so results are bit-identical from run to run.  (fp32 master gradients of
+ * the mixed-precision recipe section 2.2 adopts.) */
+int conv2d_wgrad(const conv2d_desc *desc, const void *x, const void *dy, float *dw,
+                 void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/* Loss-scale removal and overflow check (the loss scaling section 2.2 adopts):
+ * grad[i] <- grad[i] * inv_scale (one binary32 rounding) for i < n, in place, every
+ * element written; *found_nonfinite (device int32) <- 1 if any grad[i] was +inf, -inf or
+ * NaN BEFORE scaling, else 0.  The flag is cleared on the stream by this call.
+ * n = 0 is legal (flag becomes 0, grad may be NULL).  inv_scale must be finite and > 0. */
+int grad_unscale_check(float *grad, size_t n, float inv_scale, int32_t *found_nonfinite,
+                       void *hip_stream);
+
+/* Static, human-readable text for a status code. */
+const char *sdconv_status_string(int status);
+
+/* hipError_t (as int) of the last SDCONV_EHIP returned on the calling thread, else 0. */
+int sdconv_last_hip_error(void);
+
+/* Name of the kernel variant the dispatcher picks for (desc, pass), e.g. for profiles.
+ * Static string; "invalid" for a bad descriptor. */
+const char *sdconv_kernel_name(const conv2d_desc *desc, int pass);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SDCONV_H */

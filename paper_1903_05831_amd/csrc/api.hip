@@ -1,0 +1,151 @@
+// C-ABI entry points of libsdconv: argument validation, kernel selection, launches.
+#include "common.h"
+#include <math.h>
+
+using namespace sdconv;
+
+static thread_local int g_last_hip_error = 0;
+
+static int hip_status(hipError_t e)
+{
+    if (e == hipSuccess) return SDCONV_OK;
+    g_last_hip_error = (int)e;
+    return SDCONV_EHIP;
+}
+
+static bool desc_shape(const conv2d_desc* d, int* Ho, int* Wo)
+{
+    if (!d) return false;
+    if (d->N < 1 || d->H < 1 || d->W < 1 || d->C < 1 || d->K < 1 || d->R < 1 || d->S < 1) return false;
+    if (d->stride_h < 1 || d->stride_w < 1 || d->dil_h < 1 || d->dil_w < 1) return false;
+    if (d->pad_h < 0 || d->pad_w < 0) return false;
+    long eh = (long)d->H + 2L * d->pad_h - (long)d->dil_h * (d->R - 1) - 1;
+    long ew = (long)d->W + 2L * d->pad_w - (long)d->dil_w * (d->S - 1) - 1;
+    if (eh < 0 || ew < 0) return false;
+    long ho = eh / d->stride_h + 1, wo = ew / d->stride_w + 1;
+    const long lim = 0x7fffffffL;
+    long nx = (long)d->N * d->H;
+    if (nx > lim || (nx *= d->W) > lim || (nx *= d->C) > lim) return false;
+    long ny = (long)d->N * ho;
+    if (ny > lim || (ny *= wo) > lim || (ny *= d->K) > lim) return false;
+    long nw = (long)d->K * d->R;
+    if (nw > lim || (nw *= d->S) > lim || (nw *= d->C) > lim) return false;
+    *Ho = (int)ho;
+    *Wo = (int)wo;
+    return true;
+}
+
+static bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+extern "C" __attribute__((visibility("default"))) int conv2d_out_shape(const conv2d_desc* desc, int32_t* Ho, int32_t* Wo)
+{
+    int ho, wo;
+    if (!Ho || !Wo || !desc_shape(desc, &ho, &wo)) return SDCONV_EINVAL;
+    *Ho = ho;
+    *Wo = wo;
+    return SDCONV_OK;
+}
+
+extern "C" __attribute__((visibility("default"))) size_t conv2d_workspace_bytes(const conv2d_desc* desc, int pass)
+{
+    int ho, wo;
+    if (!desc_shape(desc, &ho, &wo)) return 0;
+    Geom g = make_geom(*desc, ho, wo);
+    switch (pass) {
+        case SDCONV_FWD: return plan_fwd(g).workspace_bytes;
+        case SDCONV_DGRAD: return plan_dgrad(g).workspace_bytes;
+        case SDCONV_WGRAD: return plan_wgrad(g).workspace_bytes;
+        default: return 0;
+    }
+}
+
+static int check_common(const conv2d_desc* desc, const void* a, const void* b, const void* out,
+                        void* ws, size_t ws_bytes, size_t need, int* Ho, int* Wo)
+{
+    if (!desc_shape(desc, Ho, Wo)) return SDCONV_EINVAL;
+    if (!a || !b || !out) return SDCONV_EINVAL;
+    if (!aligned16(a) || !aligned16(b) || !aligned16(out)) return SDCONV_EINVAL;
+    if (need) {
+        if (!ws || ws_bytes < need) return SDCONV_EWORKSPACE;
+        if (reinterpret_cast<uintptr_t>(ws) & 255u) return SDCONV_EINVAL;
+    }
+    return SDCONV_OK;
+}
+
+extern "C" __attribute__((visibility("default"))) int conv2d_fwd(const conv2d_desc* desc, const void* x, const void* w, void* y,
+                          void* workspace, size_t workspace_bytes, void* hip_stream)
+{
+    int Ho, Wo;
+    if (!desc_shape(desc, &Ho, &Wo)) return SDCONV_EINVAL;
+    Geom g = make_geom(*desc, Ho, Wo);
+    Plan p = plan_fwd(g);
+    int rc = check_common(desc, x, w, y, workspace, workspace_bytes, p.workspace_bytes, &Ho, &Wo);
+    if (rc) return rc;
+    return hip_status(run_fwd(g, p, (const __half*)x, (const __half*)w, (__half*)y, workspace,
+                              (hipStream_t)hip_stream));
+}
+
+extern "C" __attribute__((visibility("default"))) int conv2d_dgrad(const conv2d_desc* desc, const void* dy, const void* w, void* dx,
+                            void* workspace, size_t workspace_bytes, void* hip_stream)
+{
+    int Ho, Wo;
+    if (!desc_shape(desc, &Ho, &Wo)) return SDCONV_EINVAL;
+    Geom g = make_geom(*desc, Ho, Wo);
+    Plan p = plan_dgrad(g);
+    int rc = check_common(desc, dy, w, dx, workspace, workspace_bytes, p.workspace_bytes, &Ho, &Wo);
+    if (rc) return rc;
+    return hip_status(run_dgrad(g, p, (const __half*)dy, (const __half*)w, (__half*)dx, workspace,
+                                (hipStream_t)hip_stream));
+}
+
+extern "C" __attribute__((visibility("default"))) int conv2d_wgrad(const conv2d_desc* desc, const void* x, const void* dy, float* dw,
+                            void* workspace, size_t workspace_bytes, void* hip_stream)
+{
+    int Ho, Wo;
+    if (!desc_shape(desc, &Ho, &Wo)) return SDCONV_EINVAL;
+    Geom g = make_geom(*desc, Ho, Wo);
+    Plan p = plan_wgrad(g);
+    int rc = check_common(desc, x, dy, dw, workspace, workspace_bytes, p.workspace_bytes, &Ho, &Wo);
+    if (rc) return rc;
+    return hip_status(run_wgrad(g, p, (const __half*)x, (const __half*)dy, dw, workspace,
+                                (hipStream_t)hip_stream));
+}
+
+extern "C" __attribute__((visibility("default"))) int grad_unscale_check(float* grad, size_t n, float inv_scale, int32_t* found_nonfinite,
+                                  void* hip_stream)
+{
+    if (!found_nonfinite) return SDCONV_EINVAL;
+    if (n > 0 && !grad) return SDCONV_EINVAL;
+    if (reinterpret_cast<uintptr_t>(grad) & 3u) return SDCONV_EINVAL;
+    if (reinterpret_cast<uintptr_t>(found_nonfinite) & 3u) return SDCONV_EINVAL;
+    if (!isfinite(inv_scale) || !(inv_scale > 0.f)) return SDCONV_EINVAL;
+    if (n >= ((size_t)1 << 40)) return SDCONV_EINVAL;
+    return hip_status(launch_unscale_check(grad, n, inv_scale, found_nonfinite, (hipStream_t)hip_stream));
+}
+
+extern "C" __attribute__((visibility("default"))) const char* sdconv_status_string(int status)
+{
+    switch (status) {
+        case SDCONV_OK: return "ok";
+        case SDCONV_EINVAL: return "invalid argument";
+        case SDCONV_EUNSUPPORTED: return "unsupported configuration";
+        case SDCONV_EWORKSPACE: return "workspace missing or too small";
+        case SDCONV_EHIP: return "HIP runtime error";
+        default: return "unknown status";
+    }
+}
+
+extern "C" __attribute__((visibility("default"))) int sdconv_last_hip_error(void) { return g_last_hip_error; }
+
+extern "C" __attribute__((visibility("default"))) const char* sdconv_kernel_name(const conv2d_desc* desc, int pass)
+{
+    int ho, wo;
+    if (!desc_shape(desc, &ho, &wo)) return "invalid";
+    Geom g = make_geom(*desc, ho, wo);
+    switch (pass) {
+        case SDCONV_FWD: return plan_fwd(g).name;
+        case SDCONV_DGRAD: return plan_dgrad(g).name;
+        case SDCONV_WGRAD: return plan_wgrad(g).name;
+        default: return "invalid";
+    }
+}

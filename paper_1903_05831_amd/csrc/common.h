@@ -1,0 +1,50 @@
+// Internal declarations shared by the HIP translation units of libsdconv.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <hip/hip_fp16.h>
+#include <stdint.h>
+#include "sdconv.h"
+
+namespace sdconv {
+
+// Problem geometry handed to kernels by value.
+struct Geom {
+    int N, H, W, C;
+    int K, R, S;
+    int sh, sw, ph, pw, dh, dw;
+    int Ho, Wo;
+};
+
+inline Geom make_geom(const conv2d_desc& d, int Ho, int Wo)
+{
+    Geom g;
+    g.N = d.N; g.H = d.H; g.W = d.W; g.C = d.C;
+    g.K = d.K; g.R = d.R; g.S = d.S;
+    g.sh = d.stride_h; g.sw = d.stride_w; g.ph = d.pad_h; g.pw = d.pad_w;
+    g.dh = d.dil_h; g.dw = d.dil_w; g.Ho = Ho; g.Wo = Wo;
+    return g;
+}
+
+// What the dispatcher decided for one (geometry, pass).
+enum Route { ROUTE_DIRECT = 0, ROUTE_IGEMM = 1 };
+struct Plan {
+    Route route;
+    int variant;             // tile variant index within the route
+    int splits;              // wgrad: number of pixel-range partial sums
+    size_t workspace_bytes;  // device scratch the pass needs
+    const char* name;        // kernel variant name, static string
+};
+Plan plan_fwd(const Geom& g);
+Plan plan_dgrad(const Geom& g);
+Plan plan_wgrad(const Geom& g);
+hipError_t run_fwd(const Geom& g, const Plan& p, const __half* x, const __half* w, __half* y, void* ws, hipStream_t st);
+hipError_t run_dgrad(const Geom& g, const Plan& p, const __half* dy, const __half* w, __half* dx, void* ws, hipStream_t st);
+hipError_t run_wgrad(const Geom& g, const Plan& p, const __half* x, const __half* dy, float* dw, void* ws, hipStream_t st);
+
+// Launchers return hipGetLastError() of their launches.  All work goes to `st`.
+hipError_t launch_direct_fwd(const Geom& g, const __half* x, const __half* w, __half* y, hipStream_t st);
+hipError_t launch_direct_dgrad(const Geom& g, const __half* dy, const __half* w, __half* dx, hipStream_t st);
+hipError_t launch_direct_wgrad(const Geom& g, const __half* x, const __half* dy, float* dw, hipStream_t st);
+hipError_t launch_unscale_check(float* grad, size_t n, float inv_scale, int32_t* flag, hipStream_t st);
+
+}  // namespace sdconv
