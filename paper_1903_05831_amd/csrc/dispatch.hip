@@ -1,29 +1,96 @@
 // Kernel selection: which route and tile variant serves a given geometry and pass.
 #include "common.h"
+#include "igemm.h"
 #include <stdlib.h>
 
 namespace sdconv {
 
+static int env_int(const char* name, int dflt)
+{
+    const char* e = getenv(name);
+    return (e && *e) ? atoi(e) : dflt;
+}
+
 static bool force_direct()
 {
     static int v = -1;
-    if (v < 0) {
-        const char* e = getenv("SDCONV_FORCE_DIRECT");
-        v = (e && e[0] == '1') ? 1 : 0;
-    }
+    if (v < 0) v = env_int("SDCONV_FORCE_DIRECT", 0) ? 1 : 0;
     return v == 1;
+}
+
+static int forced_variant()
+{
+    static int v = -2;
+    if (v == -2) v = env_int("SDCONV_IGEMM_VARIANT", -1);
+    return v;
+}
+
+static size_t align256(size_t b) { return (b + 255) & ~(size_t)255; }
+
+// The MFMA route moves 16-byte (8-half) vectors along the channel axis of every tensor.
+static bool igemm_ok(const Geom& g)
+{
+    if (force_direct()) return false;
+    if (g.C % 8 || g.K % 8) return false;
+    if (g.R * g.S > kMaxTaps) return false;
+    return true;
+}
+
+// Row tiles of the fwd/dgrad index space for a tile height bm.
+static int row_tiles(const Geom& g, bool dgrad, int bm, int* starts, int* nclasses)
+{
+    if (!dgrad) {
+        long M = (long)g.N * g.Ho * g.Wo;
+        starts[0] = 0;
+        starts[1] = (int)((M + bm - 1) / bm);
+        *nclasses = 1;
+        return starts[1];
+    }
+    int nc = g.sh * g.sw, acc = 0;
+    for (int q = 0; q < nc; ++q) {
+        int a = q / g.sw, b = q % g.sw;
+        long Hi = (g.H - a + g.sh - 1) / g.sh, Wj = (g.W - b + g.sw - 1) / g.sw;
+        if (Hi < 0) Hi = 0;
+        if (Wj < 0) Wj = 0;
+        long M = (long)g.N * Hi * Wj;
+        starts[q] = acc;
+        acc += (int)((M + bm - 1) / bm);
+    }
+    starts[nc] = acc;
+    *nclasses = nc;
+    return acc;
+}
+
+static int pick_variant(const Geom& g, bool dgrad)
+{
+    int fv = forced_variant();
+    if (fv >= 0 && fv < kNumIgemmVariants) return fv;
+    int nout = dgrad ? g.C : g.K;
+    // Narrow filters: a 64-wide tile wastes nothing; otherwise 128 columns.  Prefer the
+    // taller tile when it still yields at least two workgroups per compute unit.
+    int starts[kMaxClasses + 1], nc;
+    if (nout <= 64) {
+        int t = row_tiles(g, dgrad, 256, starts, &nc);
+        return (t >= 512) ? 2 : 3;
+    }
+    int tn = (nout + 127) / 128;
+    int t = row_tiles(g, dgrad, 256, starts, &nc) * tn;
+    return (t >= 512) ? 1 : 0;
 }
 
 Plan plan_fwd(const Geom& g)
 {
-    (void)g; (void)force_direct;
-    return Plan{ROUTE_DIRECT, 0, 1, 0, "direct_fwd"};
+    if (!igemm_ok(g)) return Plan{ROUTE_DIRECT, 0, 1, 0, "direct_fwd"};
+    int v = pick_variant(g, false);
+    return Plan{ROUTE_IGEMM, v, 1, 0, kIgemmVariants[v].name};
 }
 
 Plan plan_dgrad(const Geom& g)
 {
-    (void)g;
-    return Plan{ROUTE_DIRECT, 0, 1, 0, "direct_dgrad"};
+    if (!igemm_ok(g) || g.sh * g.sw > kMaxClasses) return Plan{ROUTE_DIRECT, 0, 1, 0, "direct_dgrad"};
+    int v = pick_variant(g, true);
+    size_t ws = align256((size_t)g.K * g.R * g.S * g.C * sizeof(__half));
+    return Plan{ROUTE_IGEMM, v, 1, ws, kIgemmVariants[v].name};
 }
 
 Plan plan_wgrad(const Geom& g)
@@ -32,16 +99,39 @@ Plan plan_wgrad(const Geom& g)
     return Plan{ROUTE_DIRECT, 0, 1, 0, "direct_wgrad"};
 }
 
+static hipError_t run_igemm(const Geom& g, const Plan& p, bool dgrad, const __half* A, const __half* B,
+                            __half* D, hipStream_t st)
+{
+    IgemmParams P;
+    P.A = A; P.B = B; P.D = D;
+    P.NB = g.N;
+    if (!dgrad) { P.Hs = g.H; P.Ws = g.W; P.Cs = g.C; P.Hd = g.Ho; P.Wd = g.Wo; P.Cd = g.K; }
+    else        { P.Hs = g.Ho; P.Ws = g.Wo; P.Cs = g.K; P.Hd = g.H; P.Wd = g.W; P.Cd = g.C; }
+    P.R = g.R; P.S = g.S;
+    P.sh = g.sh; P.sw = g.sw; P.ph = g.ph; P.pw = g.pw; P.dh = g.dh; P.dw = g.dw;
+    P.mode = dgrad ? 1 : 0;
+    P.sw_cls = dgrad ? g.sw : 1;
+    const IgemmVariant& v = kIgemmVariants[p.variant];
+    int tiles_m = row_tiles(g, dgrad, v.bm, P.class_tile_start, &P.nclasses);
+    P.tiles_n = (P.Cd + v.bn - 1) / v.bn;
+    P.b_row_pitch = g.R * g.S * P.Cs;
+    return launch_igemm(p.variant, P, tiles_m * P.tiles_n, st);
+}
+
 hipError_t run_fwd(const Geom& g, const Plan& p, const __half* x, const __half* w, __half* y, void* ws, hipStream_t st)
 {
-    (void)p; (void)ws;
-    return launch_direct_fwd(g, x, w, y, st);
+    (void)ws;
+    if (p.route == ROUTE_DIRECT) return launch_direct_fwd(g, x, w, y, st);
+    return run_igemm(g, p, false, x, w, y, st);
 }
 
 hipError_t run_dgrad(const Geom& g, const Plan& p, const __half* dy, const __half* w, __half* dx, void* ws, hipStream_t st)
 {
-    (void)p; (void)ws;
-    return launch_direct_dgrad(g, dy, w, dx, st);
+    if (p.route == ROUTE_DIRECT) return launch_direct_dgrad(g, dy, w, dx, st);
+    __half* wT = static_cast<__half*>(ws);
+    hipError_t e = launch_filter_transpose(w, wT, g.K, g.R * g.S, g.C, st);
+    if (e != hipSuccess) return e;
+    return run_igemm(g, p, true, dy, wT, dx, st);
 }
 
 hipError_t run_wgrad(const Geom& g, const Plan& p, const __half* x, const __half* dy, float* dw, void* ws, hipStream_t st)

@@ -1,0 +1,34 @@
+// Parameters of the implicit-GEMM forward / data-gradient kernel.
+#pragma once
+#include "common.h"
+
+namespace sdconv {
+
+constexpr int kMaxTaps = 64;      // R*S the MFMA route accepts
+constexpr int kMaxClasses = 16;   // stride_h*stride_w parity classes of a strided dgrad
+
+struct IgemmParams {
+    const __half* A;   // gathered activations: x (forward) or dy (data gradient)
+    const __half* B;   // filter matrix, one row per destination channel: [Cd][R][S][Cs]
+    __half* D;         // destination activations
+    int NB;            // batch
+    int Hs, Ws, Cs;    // source image extents and channels (contraction channels per tap)
+    int Hd, Wd, Cd;    // destination image extents and channels
+    int R, S;
+    int sh, sw, ph, pw, dh, dw;
+    int mode;          // 0 forward, 1 data gradient
+    int nclasses;      // 1, or stride_h*stride_w for a data gradient
+    int sw_cls;        // classes along w (stride_w for a data gradient, else 1)
+    int tiles_n;       // column tiles
+    int b_row_pitch;   // R*S*Cs
+    int class_tile_start[kMaxClasses + 1];   // first row-tile of each class, then the total
+};
+
+struct IgemmVariant { int bm, bn; const char* name; };
+constexpr int kNumIgemmVariants = 4;
+extern const IgemmVariant kIgemmVariants[kNumIgemmVariants];
+
+hipError_t launch_igemm(int variant, const IgemmParams& P, int total_tiles, hipStream_t st);
+hipError_t launch_filter_transpose(const __half* w, __half* wT, int K, int RS, int C, hipStream_t st);
+
+}  // namespace sdconv
