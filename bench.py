@@ -1,0 +1,205 @@
+#!/usr/bin/env python3
+"""Benchmark of the mixed-precision convolution hot path on one MI355X.
+
+One step = one pass of the whole path over the full ResNet-50-C4 Faster R-CNN conv
+workload (N=2 images of 800x1344 plus 512 RoIs; 53 conv layers): conv2d_fwd, conv2d_dgrad
+and conv2d_wgrad for every layer, then grad_unscale_check over all 23 454 912 fp32
+weight-gradient elements.  Inputs are synthetic (N(0,1) activations and gradients,
+He-normal weights), generated on the device before the timed region.
+
+Prints ONE JSON line.  `value` is algorithmic TFLOP/s of the whole step (2*N*Ho*Wo*K*R*S*C
+per pass and layer).  `roofline` is for the kernel with the largest share of the step,
+timed with HIP events on the launch stream.  `cpu_baseline` times the fp64 CPU oracle on a
+bounded sample of the same workload.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+PEAK_F16_TFLOPS = 2516.6     # 256 CUs x 4096 FLOP/clk x 2.4 GHz, dense fp16 MFMA
+PEAK_HBM_GBS = 8000.0
+CONFIG_ID = 5
+LOSS_SCALE = 1024.0
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--detail", type=str, default="", help="write per-layer timings (JSON) to this file")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on exactly one GPU (no collectives are part of it); use --gpus 1",
+              file=sys.stderr)
+        return 2
+
+    import torch
+    import paper_1903_05831_amd as sd
+    from paper_1903_05831_amd import workloads
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        return 2
+    sd.lib()   # fail loudly when the HIP library is missing
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    stream = torch.cuda.current_stream().cuda_stream
+    layers = workloads.CONFIGS[CONFIG_ID]
+
+    # ---- device-resident synthetic inputs --------------------------------------------------
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(workloads.BASE_SEED)
+    dw_total = sum(l.dw_numel for l in layers)
+    dw_flat = torch.empty(dw_total, dtype=torch.float32, device=dev)
+    flag = torch.zeros(1, dtype=torch.int32, device=dev)
+    ws_bytes = 256
+    jobs = []
+    off = 0
+    for l in layers:
+        d = sd.desc_of(l)
+        x = torch.randn(l.x_shape, generator=gen, device=dev, dtype=torch.float32).half()
+        w = (torch.randn(l.w_shape, generator=gen, device=dev, dtype=torch.float32)
+             * (2.0 / (l.R * l.S * l.C)) ** 0.5).half()
+        g = torch.randn(l.y_shape, generator=gen, device=dev, dtype=torch.float32).half()
+        y = torch.empty(l.y_shape, dtype=torch.float16, device=dev)
+        dx = torch.empty(l.x_shape, dtype=torch.float16, device=dev)
+        dw = dw_flat[off:off + l.dw_numel]
+        off += l.dw_numel
+        for pid in (sd.FWD, sd.DGRAD, sd.WGRAD):
+            ws_bytes = max(ws_bytes, sd.conv2d_workspace_bytes(d, pid))
+        jobs.append((l, d, x, w, g, y, dx, dw))
+    ws = torch.empty(ws_bytes, dtype=torch.uint8, device=dev)
+    inv_scale = 1.0 / LOSS_SCALE
+
+    calls = []   # (layer, pass name, kernel name, flops, closure)
+    for (l, d, x, w, g, y, dx, dw) in jobs:
+        calls.append((l, "fwd", sd.kernel_name(d, sd.FWD), l.flops,
+                      lambda d=d, x=x, w=w, y=y: sd.conv2d_fwd(d, x, w, y, ws, stream)))
+        calls.append((l, "dgrad", sd.kernel_name(d, sd.DGRAD), l.flops,
+                      lambda d=d, g=g, w=w, dx=dx: sd.conv2d_dgrad(d, g, w, dx, ws, stream)))
+        calls.append((l, "wgrad", sd.kernel_name(d, sd.WGRAD), l.flops,
+                      lambda d=d, x=x, g=g, dw=dw: sd.conv2d_wgrad(d, x, g, dw, ws, stream)))
+
+    def unscale():
+        sd.grad_unscale_check(dw_flat, dw_total, inv_scale, flag, stream)
+
+    def step():
+        for c in calls:
+            c[4]()
+        unscale()
+
+    flops_per_step = 3 * sum(l.flops for l in layers)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+    value = flops_per_step / (ms_per_step * 1e-3) / 1e12
+
+    # ---- per-call HIP-event timing (second pass over the same steps) ---------------------------
+    ev = [[(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
+           for _ in range(len(calls) + 1)] for _ in range(args.steps)]
+    for s in range(args.steps):
+        for i, c in enumerate(calls):
+            ev[s][i][0].record()
+            c[4]()
+            ev[s][i][1].record()
+        ev[s][-1][0].record()
+        unscale()
+        ev[s][-1][1].record()
+    torch.cuda.synchronize()
+    groups = {}
+    per_call = []
+    for i, c in enumerate(calls):
+        ms = sum(ev[s][i][0].elapsed_time(ev[s][i][1]) for s in range(args.steps)) / args.steps
+        per_call.append({"layer": c[0].name, "pass": c[1], "kernel": c[2], "us": ms * 1e3,
+                         "tflops": c[3] / ms / 1e9, "pct_peak": 100 * c[3] / ms / 1e9 / PEAK_F16_TFLOPS})
+        gk = groups.setdefault(c[2], {"ms": 0.0, "flops": 0.0, "launches": 0, "pass": c[1]})
+        gk["ms"] += ms
+        gk["flops"] += c[3]
+        gk["launches"] += 1
+    unscale_ms = sum(ev[s][-1][0].elapsed_time(ev[s][-1][1]) for s in range(args.steps)) / args.steps
+    instrumented_ms = sum(g["ms"] for g in groups.values()) + unscale_ms
+
+    # dominant kernel: largest share of the step among single-kernel calls (forward launches
+    # are exactly one kernel per event pair)
+    fwd_groups = {k: g for k, g in groups.items() if g["pass"] == "fwd"}
+    dom_name, dom = max(fwd_groups.items(), key=lambda kv: kv[1]["ms"])
+    dom_avg_ms = dom["ms"] / dom["launches"]
+    dom_flops = dom["flops"] / dom["launches"]
+    achieved = dom_flops / dom_avg_ms / 1e9
+    roofline = {"kernel": dom_name, "bound": "mfma", "achieved": achieved, "peak": PEAK_F16_TFLOPS,
+                "unit": "TFLOP/s", "frac": achieved / PEAK_F16_TFLOPS, "traffic": None,
+                "avg_launch_us": dom_avg_ms * 1e3, "launches_per_step": dom["launches"],
+                "flop_per_launch": dom_flops}
+    unscale_gbs = 8.0 * dw_total / unscale_ms / 1e6
+
+    # ---- the named target layers: 3x3 convs of res3/res4 ----------------------------------------
+    targets = [p for p in per_call if p["layer"].endswith("b") and p["layer"].startswith(("res3", "res4"))]
+    tgt_flops = sum(next(l.flops for l in layers if l.name == p["layer"]) for p in targets)
+    tgt_ms = sum(p["us"] for p in targets) / 1e3
+    target_pct = 100 * tgt_flops / tgt_ms / 1e9 / PEAK_F16_TFLOPS if tgt_ms > 0 else None
+
+    out = {
+        "metric": "conv TFLOP/s (fwd+dgrad+wgrad) on ResNet-50-C4 shapes; % fp16 MFMA peak",
+        "value": value, "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f16", "data": "synthetic",
+        "config": {"workload": "configs[4]: " + workloads.CONFIG_NAMES[CONFIG_ID],
+                   "layers": len(layers), "gflop_per_step": flops_per_step / 1e9,
+                   "passes": "fwd+dgrad+wgrad per layer, then grad_unscale_check on %d fp32" % dw_total,
+                   "loss_scale": LOSS_SCALE},
+        "pct_fp16_mfma_peak": 100 * value / PEAK_F16_TFLOPS,
+        "pct_peak_res3_res4_3x3": target_pct,
+        "roofline": roofline,
+        "unscale": {"us": unscale_ms * 1e3, "GBps": unscale_gbs, "frac_hbm": unscale_gbs / PEAK_HBM_GBS,
+                    "bytes": 8 * dw_total},
+        "ms_per_step_with_events": instrumented_ms,
+        "kernels": {k: {"ms_per_step": g["ms"], "launches": g["launches"],
+                        "tflops": g["flops"] / g["ms"] / 1e9} for k, g in sorted(groups.items())},
+        "paper_context": "Fig. 1(b): 2.0x FP32->FP16 end-to-end training speedup, hardware not stated",
+    }
+
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline()
+    if args.detail:
+        with open(args.detail, "w") as f:
+            json.dump(per_call, f, indent=1)
+    print(json.dumps(out))
+    return 0
+
+
+def cpu_baseline() -> dict:
+    """The CPU oracle as it stands, timed on all three passes of one res4 3x3 layer (256->256
+    at 50x84, N=2; 29.7 GFLOP in total), the layer the whole-workload target is set on."""
+    import oracle
+    from paper_1903_05831_amd import workloads
+    li, l = next((i, l) for i, l in enumerate(workloads.CONFIGS[4]) if l.name == "res4.1b")
+    x, w, g = workloads.make_x(l, 4, li), workloads.make_w(l, 4, li), workloads.make_g(l, 4, li)
+    d = oracle.make_desc(l.N, l.H, l.W, l.C, l.K, l.R, l.S, (l.stride,) * 2, (l.pad,) * 2, (l.dil,) * 2)
+    t0 = time.perf_counter()
+    oracle.conv2d_fwd(d, x, w)
+    oracle.conv2d_dgrad(d, g, w)
+    oracle.conv2d_wgrad(d, x, g)
+    dt = time.perf_counter() - t0
+    return {"value": 3 * l.flops / dt / 1e12, "unit": "TFLOP/s", "cores": oracle.num_threads(),
+            "kind": "oracle", "seconds": dt,
+            "sample": "res4.1b (3x3 256->256, N=2, 50x84): fwd+dgrad+wgrad in full, fp64, %.1f GFLOP" % (3 * l.flops / 1e9)}
+
+
+if __name__ == "__main__":
+    sys.exit(main())

@@ -1,6 +1,7 @@
 // Kernel selection: which route and tile variant serves a given geometry and pass.
 #include "common.h"
 #include "igemm.h"
+#include "wgrad.h"
 #include <stdlib.h>
 
 namespace sdconv {
@@ -82,7 +83,7 @@ Plan plan_fwd(const Geom& g)
 {
     if (!igemm_ok(g)) return Plan{ROUTE_DIRECT, 0, 1, 0, "direct_fwd"};
     int v = pick_variant(g, false);
-    return Plan{ROUTE_IGEMM, v, 1, 0, kIgemmVariants[v].name};
+    return Plan{ROUTE_IGEMM, v, 1, 0, kIgemmVariants[v].fwd_name};
 }
 
 Plan plan_dgrad(const Geom& g)
@@ -90,13 +91,36 @@ Plan plan_dgrad(const Geom& g)
     if (!igemm_ok(g) || g.sh * g.sw > kMaxClasses) return Plan{ROUTE_DIRECT, 0, 1, 0, "direct_dgrad"};
     int v = pick_variant(g, true);
     size_t ws = align256((size_t)g.K * g.R * g.S * g.C * sizeof(__half));
-    return Plan{ROUTE_IGEMM, v, 1, ws, kIgemmVariants[v].name};
+    return Plan{ROUTE_IGEMM, v, 1, ws, kIgemmVariants[v].dgrad_name};
+}
+
+// Pixel-range count for the weight gradient: enough workgroups to fill the chip a few times
+// over, but at least four 64-pixel steps per range.
+static void wgrad_split(const Geom& g, int variant, int* splits, int* steps_per_split)
+{
+    const WgradVariant& v = kWgradVariants[variant];
+    long tiles = (long)((g.K + v.bm - 1) / v.bm) * ((g.C + v.bn - 1) / v.bn) * g.R * g.S;
+    long P = (long)g.N * g.Ho * g.Wo;
+    long total_steps = (P + 63) / 64;
+    static int target = env_int("SDCONV_WGRAD_TARGET_BLOCKS", 768);
+    long want = (target + tiles - 1) / tiles;
+    long cap = total_steps / 4;
+    if (cap < 1) cap = 1;
+    if (want > cap) want = cap;
+    if (want < 1) want = 1;
+    long sps = (total_steps + want - 1) / want;
+    *steps_per_split = (int)sps;
+    *splits = (int)((total_steps + sps - 1) / sps);
 }
 
 Plan plan_wgrad(const Geom& g)
 {
-    (void)g;
-    return Plan{ROUTE_DIRECT, 0, 1, 0, "direct_wgrad"};
+    if (!igemm_ok(g)) return Plan{ROUTE_DIRECT, 0, 1, 0, "direct_wgrad"};
+    int v = (g.K <= 64) ? 1 : 0;
+    int splits, sps;
+    wgrad_split(g, v, &splits, &sps);
+    size_t ws = splits > 1 ? align256((size_t)splits * g.K * g.R * g.S * g.C * sizeof(float)) : 0;
+    return Plan{ROUTE_IGEMM, v, splits, ws, kWgradVariants[v].name};
 }
 
 static hipError_t run_igemm(const Geom& g, const Plan& p, bool dgrad, const __half* A, const __half* B,
@@ -136,8 +160,21 @@ hipError_t run_dgrad(const Geom& g, const Plan& p, const __half* dy, const __hal
 
 hipError_t run_wgrad(const Geom& g, const Plan& p, const __half* x, const __half* dy, float* dw, void* ws, hipStream_t st)
 {
-    (void)p; (void)ws;
-    return launch_direct_wgrad(g, x, dy, dw, st);
+    if (p.route == ROUTE_DIRECT) return launch_direct_wgrad(g, x, dy, dw, st);
+    const WgradVariant& v = kWgradVariants[p.variant];
+    WgradParams P;
+    P.X = x; P.G = dy;
+    P.N = g.N; P.H = g.H; P.W = g.W; P.C = g.C; P.K = g.K; P.R = g.R; P.S = g.S;
+    P.sh = g.sh; P.sw = g.sw; P.ph = g.ph; P.pw = g.pw; P.dh = g.dh; P.dw = g.dw;
+    P.Ho = g.Ho; P.Wo = g.Wo;
+    P.P = g.N * g.Ho * g.Wo;
+    wgrad_split(g, p.variant, &P.splits, &P.steps_per_split);
+    P.tiles_k = (g.K + v.bm - 1) / v.bm;
+    P.tiles_c = (g.C + v.bn - 1) / v.bn;
+    P.out = (P.splits > 1) ? static_cast<float*>(ws) : dw;
+    hipError_t e = launch_wgrad(p.variant, P, st);
+    if (e != hipSuccess || P.splits == 1) return e;
+    return launch_splitk_reduce(static_cast<const float*>(ws), dw, P.splits, (long)g.K * g.R * g.S * g.C, st);
 }
 
 }  // namespace sdconv

@@ -24,7 +24,7 @@ struct IgemmParams {
     int class_tile_start[kMaxClasses + 1];   // first row-tile of each class, then the total
 };
 
-struct IgemmVariant { int bm, bn; const char* name; };
+struct IgemmVariant { int bm, bn; const char* fwd_name; const char* dgrad_name; };
 constexpr int kNumIgemmVariants = 4;
 extern const IgemmVariant kIgemmVariants[kNumIgemmVariants];
 

@@ -32,7 +32,9 @@ constexpr int kBK = 64;            // contraction halves per step
 constexpr int kRowBytes = kBK * 2; // 128
 constexpr int kThreads = 256;
 
-template <int BM, int BN, int WGM, int WGN>
+// MODE 0: forward (rows are output pixels, source = x).  MODE 1: data gradient (rows are
+// input pixels of one parity class, source = dy).
+template <int MODE, int BM, int BN, int WGM, int WGN>
 __global__ __launch_bounds__(kThreads) void igemm_kernel(IgemmParams P)
 {
     static_assert(WGM * WGN == 4, "four waves per workgroup");
@@ -65,7 +67,7 @@ __global__ __launch_bounds__(kThreads) void igemm_kernel(IgemmParams P)
     const int ca = cls / P.sw_cls, cb = cls % P.sw_cls;   // parity class (dgrad) or (0,0)
 
     int Hi, Wj, mh, mw, eh, ew;
-    if (P.mode == 0) { Hi = P.Hd; Wj = P.Wd; mh = P.sh; mw = P.sw; eh = 1; ew = 1; }
+    if (MODE == 0) { Hi = P.Hd; Wj = P.Wd; mh = P.sh; mw = P.sw; eh = 1; ew = 1; }
     else {
         Hi = (P.Hd - ca + P.sh - 1) / P.sh; Wj = (P.Wd - cb + P.sw - 1) / P.sw;
         mh = 1; mw = 1; eh = P.sh; ew = P.sw;
@@ -80,7 +82,7 @@ __global__ __launch_bounds__(kThreads) void igemm_kernel(IgemmParams P)
         int oh = 0, ow = 0;
         const int r = lane / P.S, s = lane % P.S;
         if (lane < ntap_all) {
-            if (P.mode == 0) { ok = true; oh = r * P.dh - P.ph; ow = s * P.dw - P.pw; }
+            if (MODE == 0) { ok = true; oh = r * P.dh - P.ph; ow = s * P.dw - P.pw; }
             else {
                 int th = ca + P.ph - r * P.dh, tw = cb + P.pw - s * P.dw;
                 ok = (th % P.sh == 0) && (tw % P.sw == 0);
@@ -252,35 +254,40 @@ __global__ __launch_bounds__(256) void filter_transpose_kernel(const __half* __r
     }
 }
 
-template <int BM, int BN, int WGM, int WGN>
+template <int MODE, int BM, int BN, int WGM, int WGN>
 static hipError_t launch_variant(const IgemmParams& P, int total_tiles, hipStream_t st)
 {
     constexpr size_t lds = 2 * (BM + BN) * kRowBytes + (3 * kMaxTaps + 4) * sizeof(int);
     static bool configured = false;
     if (!configured) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&igemm_kernel<BM, BN, WGM, WGN>),
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&igemm_kernel<MODE, BM, BN, WGM, WGN>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         if (e != hipSuccess) return e;
         configured = true;
     }
-    hipLaunchKernelGGL((igemm_kernel<BM, BN, WGM, WGN>), dim3(total_tiles), dim3(kThreads), lds, st, P);
+    hipLaunchKernelGGL((igemm_kernel<MODE, BM, BN, WGM, WGN>), dim3(total_tiles), dim3(kThreads), lds, st, P);
     return hipGetLastError();
 }
 
 const IgemmVariant kIgemmVariants[kNumIgemmVariants] = {
-    {128, 128, "igemm_128x128"},
-    {256, 128, "igemm_256x128"},
-    {256, 64, "igemm_256x64"},
-    {128, 64, "igemm_128x64"},
+    {128, 128, "igemm_fwd_128x128", "igemm_dgrad_128x128"},
+    {256, 128, "igemm_fwd_256x128", "igemm_dgrad_256x128"},
+    {256, 64, "igemm_fwd_256x64", "igemm_dgrad_256x64"},
+    {128, 64, "igemm_fwd_128x64", "igemm_dgrad_128x64"},
 };
 
 hipError_t launch_igemm(int variant, const IgemmParams& P, int total_tiles, hipStream_t st)
 {
-    switch (variant) {
-        case 0: return launch_variant<128, 128, 2, 2>(P, total_tiles, st);
-        case 1: return launch_variant<256, 128, 2, 2>(P, total_tiles, st);
-        case 2: return launch_variant<256, 64, 4, 1>(P, total_tiles, st);
-        case 3: return launch_variant<128, 64, 2, 2>(P, total_tiles, st);
+    const int key = variant * 2 + (P.mode ? 1 : 0);
+    switch (key) {
+        case 0: return launch_variant<0, 128, 128, 2, 2>(P, total_tiles, st);
+        case 1: return launch_variant<1, 128, 128, 2, 2>(P, total_tiles, st);
+        case 2: return launch_variant<0, 256, 128, 2, 2>(P, total_tiles, st);
+        case 3: return launch_variant<1, 256, 128, 2, 2>(P, total_tiles, st);
+        case 4: return launch_variant<0, 256, 64, 4, 1>(P, total_tiles, st);
+        case 5: return launch_variant<1, 256, 64, 4, 1>(P, total_tiles, st);
+        case 6: return launch_variant<0, 128, 64, 2, 2>(P, total_tiles, st);
+        case 7: return launch_variant<1, 128, 64, 2, 2>(P, total_tiles, st);
         default: return hipErrorInvalidValue;
     }
 }
