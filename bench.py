@@ -184,21 +184,26 @@ def main() -> int:
 
 
 def cpu_baseline() -> dict:
-    """The CPU oracle as it stands, timed on all three passes of one res4 3x3 layer (256->256
-    at 50x84, N=2; 29.7 GFLOP in total), the layer the whole-workload target is set on."""
+    """The CPU oracle as it stands, timed on all three passes of every layer of the res4 trunk
+    (configs[3]: 19 layers, 376.5 GFLOP in total), whole tensors, fp64."""
     import oracle
     from paper_1903_05831_amd import workloads
-    li, l = next((i, l) for i, l in enumerate(workloads.CONFIGS[4]) if l.name == "res4.1b")
-    x, w, g = workloads.make_x(l, 4, li), workloads.make_w(l, 4, li), workloads.make_g(l, 4, li)
-    d = oracle.make_desc(l.N, l.H, l.W, l.C, l.K, l.R, l.S, (l.stride,) * 2, (l.pad,) * 2, (l.dil,) * 2)
-    t0 = time.perf_counter()
-    oracle.conv2d_fwd(d, x, w)
-    oracle.conv2d_dgrad(d, g, w)
-    oracle.conv2d_wgrad(d, x, g)
-    dt = time.perf_counter() - t0
-    return {"value": 3 * l.flops / dt / 1e12, "unit": "TFLOP/s", "cores": oracle.num_threads(),
-            "kind": "oracle", "seconds": dt,
-            "sample": "res4.1b (3x3 256->256, N=2, 50x84): fwd+dgrad+wgrad in full, fp64, %.1f GFLOP" % (3 * l.flops / 1e9)}
+    cfg = 4
+    flops = 0
+    seconds = 0.0
+    for li, l in enumerate(workloads.CONFIGS[cfg]):
+        x, w, g = workloads.make_x(l, cfg, li), workloads.make_w(l, cfg, li), workloads.make_g(l, cfg, li)
+        d = oracle.make_desc(l.N, l.H, l.W, l.C, l.K, l.R, l.S, (l.stride,) * 2, (l.pad,) * 2, (l.dil,) * 2)
+        t0 = time.perf_counter()
+        oracle.conv2d_fwd(d, x, w)
+        oracle.conv2d_dgrad(d, g, w)
+        oracle.conv2d_wgrad(d, x, g)
+        seconds += time.perf_counter() - t0
+        flops += 3 * l.flops
+    return {"value": flops / seconds / 1e12, "unit": "TFLOP/s", "cores": oracle.num_threads(),
+            "kind": "oracle", "seconds": seconds,
+            "sample": "configs[3] (res4 trunk, 19 conv layers, N=2): fwd+dgrad+wgrad of every layer in full, "
+                      "fp64, %.1f GFLOP" % (flops / 1e9)}
 
 
 if __name__ == "__main__":

@@ -26,7 +26,7 @@ inline Geom make_geom(const conv2d_desc& d, int Ho, int Wo)
 }
 
 // What the dispatcher decided for one (geometry, pass).
-enum Route { ROUTE_DIRECT = 0, ROUTE_IGEMM = 1 };
+enum Route { ROUTE_DIRECT = 0, ROUTE_IGEMM = 1, ROUTE_THIN = 2 };
 struct Plan {
     Route route;
     int variant;             // tile variant index within the route

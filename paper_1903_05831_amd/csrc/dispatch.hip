@@ -2,6 +2,7 @@
 #include "common.h"
 #include "igemm.h"
 #include "wgrad.h"
+#include "thin.h"
 #include <stdlib.h>
 
 namespace sdconv {
@@ -79,8 +80,11 @@ static int pick_variant(const Geom& g, bool dgrad)
     return (t >= 512) ? 1 : 0;
 }
 
+static bool thin_ok(const Geom& g) { return !force_direct() && g.C <= 4 && thin_supported(g); }
+
 Plan plan_fwd(const Geom& g)
 {
+    if (thin_ok(g)) return Plan{ROUTE_THIN, 0, 1, align256(thin_packed_filter_bytes(g)), "thin_fwd"};
     if (!igemm_ok(g)) return Plan{ROUTE_DIRECT, 0, 1, 0, "direct_fwd"};
     int v = pick_variant(g, false);
     return Plan{ROUTE_IGEMM, v, 1, 0, kIgemmVariants[v].fwd_name};
@@ -115,6 +119,7 @@ static void wgrad_split(const Geom& g, int variant, int* splits, int* steps_per_
 
 Plan plan_wgrad(const Geom& g)
 {
+    if (thin_ok(g)) return Plan{ROUTE_THIN, 0, 1, align256(thin_wgrad_partial_bytes(g)), "thin_wgrad"};
     if (!igemm_ok(g)) return Plan{ROUTE_DIRECT, 0, 1, 0, "direct_wgrad"};
     int v = (g.K <= 64) ? 1 : 0;
     int splits, sps;
@@ -144,8 +149,8 @@ static hipError_t run_igemm(const Geom& g, const Plan& p, bool dgrad, const __ha
 
 hipError_t run_fwd(const Geom& g, const Plan& p, const __half* x, const __half* w, __half* y, void* ws, hipStream_t st)
 {
-    (void)ws;
     if (p.route == ROUTE_DIRECT) return launch_direct_fwd(g, x, w, y, st);
+    if (p.route == ROUTE_THIN) return launch_thin_fwd(g, x, w, y, ws, st);
     return run_igemm(g, p, false, x, w, y, st);
 }
 
@@ -161,6 +166,7 @@ hipError_t run_dgrad(const Geom& g, const Plan& p, const __half* dy, const __hal
 hipError_t run_wgrad(const Geom& g, const Plan& p, const __half* x, const __half* dy, float* dw, void* ws, hipStream_t st)
 {
     if (p.route == ROUTE_DIRECT) return launch_direct_wgrad(g, x, dy, dw, st);
+    if (p.route == ROUTE_THIN) return launch_thin_wgrad(g, x, dy, dw, ws, st);
     const WgradVariant& v = kWgradVariants[p.variant];
     WgradParams P;
     P.X = x; P.G = dy;

@@ -1,0 +1,25 @@
+// Parameters of the thin-input (C <= 4) stem kernels.
+#pragma once
+#include "common.h"
+
+namespace sdconv {
+
+struct ThinParams {
+    const __half* X;     // input [N][H][W][C], C <= 4
+    const __half* Wp;    // packed filter bank (forward)
+    __half* Y;           // forward output
+    const __half* G;     // upstream gradient (wgrad)
+    float* partial;      // wgrad partial sums
+    int N, H, W, C, K, R, S;
+    int sh, sw, ph, pw, Ho, Wo;
+    int tiles_h, tiles_w, ntiles;   // 8x32 output tiles
+    int PH, PW;                     // LDS patch extent in padded pixels
+};
+
+bool thin_supported(const Geom& g);
+size_t thin_packed_filter_bytes(const Geom& g);
+size_t thin_wgrad_partial_bytes(const Geom& g);
+hipError_t launch_thin_fwd(const Geom& g, const __half* x, const __half* w, __half* y, void* ws, hipStream_t st);
+hipError_t launch_thin_wgrad(const Geom& g, const __half* x, const __half* dy, float* dw, void* ws, hipStream_t st);
+
+}  // namespace sdconv

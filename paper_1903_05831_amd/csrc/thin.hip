@@ -1,0 +1,380 @@
+// Convolutions whose input has at most 4 channels (image stems, e.g. 7x7 stride 2 on RGB).
+//
+// With C = 3 an NHWC pixel is 6 bytes, so neither the 16-byte gathers of the general
+// implicit-GEMM kernels nor their 64-deep contraction steps fit.  Here a workgroup copies the
+// input patch under its 8x32 output tile into LDS once, padding every pixel to 4 halves
+// (8 bytes).  One filter row then is a run of 8 padded pixels = 32 halves = two
+// v_mfma_f32_32x32x16_f16 contraction steps, read straight from the patch:
+//   forward : rows = filters (packed, zero-padded filter bank), columns = the 32 output
+//             pixels of one tile row; a lane's operand is 2 adjacent padded pixels (16 bytes).
+//   wgrad   : rows = filters (dy tile, transposing LDS read), columns = the 32 (s,c) slots of
+//             one filter row (transposing LDS read of the patch: 4 consecutive output pixels
+//             of one padded input pixel), contraction = output pixels along the tile row.
+// Both are bound by the HBM traffic of the K-channel tensor (y or dy), so the y tile is
+// written, and the dy tile read, as whole 128-byte lines.
+#include "common.h"
+#include "thin.h"
+
+namespace sdconv {
+
+typedef _Float16 half8 __attribute__((ext_vector_type(8)));
+typedef _Float16 half4 __attribute__((ext_vector_type(4)));
+typedef short short4v __attribute__((ext_vector_type(4)));
+typedef float float16v __attribute__((ext_vector_type(16)));
+typedef unsigned int uint4v __attribute__((ext_vector_type(4)));
+typedef unsigned int uint2v __attribute__((ext_vector_type(2)));
+
+constexpr int kTH = 8, kTW = 32;        // output tile (rows x columns)
+constexpr int kKT = 64;                 // filters per workgroup tile
+
+__device__ __forceinline__ half4 lds_read_tr4(const unsigned char* p)
+{
+    typedef __attribute__((address_space(3))) short4v* lds_ptr;
+    short4v v = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr)(p));
+    return __builtin_bit_cast(half4, v);
+}
+
+// Packed filter bank for the forward pass:
+//   Wp[kt][r][j][kk][e], kt = filter tile, j = 16-byte chunk 0..3 of the 32-half filter row,
+//   kk = filter within the tile (64), e = half within the chunk; slot 8j+e = 4*s + c.
+__global__ __launch_bounds__(256) void thin_pack_filter_kernel(const __half* __restrict__ w,
+                                                              __half* __restrict__ wp, int K, int R, int S, int C,
+                                                              long total)
+{
+    long i = (long)blockIdx.x * 256 + threadIdx.x;
+    if (i >= total) return;
+    int e = (int)(i & 7);
+    long t = i >> 3;
+    int kk = (int)(t % kKT); t /= kKT;
+    int j = (int)(t & 3); t >>= 2;
+    int r = (int)(t % R);
+    int kt = (int)(t / R);
+    int slot = 8 * j + e, s = slot >> 2, c = slot & 3, k = kt * kKT + kk;
+    __half v = __half(0.f);
+    if (k < K && s < S && c < C) v = w[(((long)k * R + r) * S + s) * C + c];
+    wp[i] = v;
+}
+
+// Copies the padded input patch of one output tile into LDS ([PH][PW] pixels of 8 bytes).
+__device__ __forceinline__ void load_patch(const ThinParams& P, unsigned char* patch, int n, int ho0, int wo0,
+                                           int tid)
+{
+    const unsigned short* X = reinterpret_cast<const unsigned short*>(P.X);
+    const int h0 = ho0 * P.sh - P.ph, w0 = wo0 * P.sw - P.pw;
+    for (int idx = tid; idx < P.PH * P.PW; idx += 256) {
+        int prow = idx / P.PW, pcol = idx - prow * P.PW;
+        int h = h0 + prow, w = w0 + pcol;
+        unsigned lo = 0, hi = 0;
+        if ((unsigned)h < (unsigned)P.H && (unsigned)w < (unsigned)P.W) {
+            const unsigned short* px = X + (((long)n * P.H + h) * P.W + w) * P.C;
+            lo = px[0];
+            if (P.C > 1) lo |= (unsigned)px[1] << 16;
+            if (P.C > 2) hi = px[2];
+            if (P.C > 3) hi |= (unsigned)px[3] << 16;
+        }
+        uint2v v = {lo, hi};
+        *reinterpret_cast<uint2v*>(patch + idx * 8) = v;
+    }
+}
+
+__global__ __launch_bounds__(256) void thin_fwd_kernel(ThinParams P)
+{
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+    unsigned char* ldsW = smem;                                   // [R][4][64] x 16 B
+    unsigned char* patch = ldsW + P.R * 4 * kKT * 16;             // [PH][PW] x 8 B
+    unsigned char* stage = patch + ((P.PH * P.PW * 8 + 15) & ~15);   // [256 pixels][128 B], chunk-swizzled
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int l32 = lane & 31, lhi = lane >> 5;
+
+    const int kt = blockIdx.y;
+    {   // this filter tile's packed bank: R*4*64 chunks of 16 bytes, copied as is
+        const uint4v* src = reinterpret_cast<const uint4v*>(P.Wp) + (long)kt * P.R * 4 * kKT;
+        for (int i = tid; i < P.R * 4 * kKT; i += 256) reinterpret_cast<uint4v*>(ldsW)[i] = src[i];
+    }
+
+    for (int tile = blockIdx.x; tile < P.ntiles; tile += gridDim.x) {
+        int t = tile;
+        const int tw = t % P.tiles_w; t /= P.tiles_w;
+        const int th = t % P.tiles_h;
+        const int n = t / P.tiles_h;
+        const int ho0 = th * kTH, wo0 = tw * kTW;
+
+        __syncthreads();                       // previous tile fully consumed
+        load_patch(P, patch, n, ho0, wo0, tid);
+        __syncthreads();
+
+        float16v acc[2][2];
+#pragma unroll
+        for (int a = 0; a < 2; ++a)
+#pragma unroll
+            for (int b = 0; b < 2; ++b)
+#pragma unroll
+                for (int e = 0; e < 16; ++e) acc[a][b][e] = 0.f;
+
+        for (int r = 0; r < P.R; ++r) {
+#pragma unroll
+            for (int q = 0; q < 2; ++q) {
+                half8 fa[2], fb[2];
+#pragma unroll
+                for (int row = 0; row < 2; ++row) {
+                    int prow = (2 * wave + row) * P.sh + r;
+                    int pcol = l32 * P.sw + 4 * q + 2 * lhi;
+                    const unsigned char* src = patch + (prow * P.PW + pcol) * 8;
+                    half4 p0 = *reinterpret_cast<const half4*>(src);
+                    half4 p1 = *reinterpret_cast<const half4*>(src + 8);
+                    fa[row] = __builtin_shufflevector(p0, p1, 0, 1, 2, 3, 4, 5, 6, 7);
+                }
+#pragma unroll
+                for (int kb = 0; kb < 2; ++kb)
+                    fb[kb] = *reinterpret_cast<const half8*>(ldsW + (((r * 4 + q * 2 + lhi) * kKT) + kb * 32 + l32) * 16);
+#pragma unroll
+                for (int row = 0; row < 2; ++row)
+#pragma unroll
+                    for (int kb = 0; kb < 2; ++kb)
+                        acc[row][kb] = __builtin_amdgcn_mfma_f32_32x32x16_f16(fb[kb], fa[row], acc[row][kb], 0, 0, 0);
+            }
+        }
+
+        // fp32 -> fp16 into the staging tile: pixel-major rows of 64 filters (128 bytes)
+#pragma unroll
+        for (int row = 0; row < 2; ++row) {
+            int pix = (2 * wave + row) * kTW + l32;
+#pragma unroll
+            for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    int k = kb * 32 + 8 * q + 4 * lhi;
+                    half4 h;
+                    h[0] = (_Float16)acc[row][kb][4 * q + 0];
+                    h[1] = (_Float16)acc[row][kb][4 * q + 1];
+                    h[2] = (_Float16)acc[row][kb][4 * q + 2];
+                    h[3] = (_Float16)acc[row][kb][4 * q + 3];
+                    int chunk = (k >> 3) ^ (pix & 7);
+                    *reinterpret_cast<half4*>(stage + pix * 128 + chunk * 16 + (k & 7) * 2) = h;
+                }
+        }
+        __syncthreads();
+        // whole 128-byte lines out: 8 lanes per pixel
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            int c = tid + 256 * i;
+            int pix = c >> 3, part = c & 7;
+            int ho = ho0 + pix / kTW, wo = wo0 + pix % kTW;
+            int k = kt * kKT + part * 8;
+            if (ho < P.Ho && wo < P.Wo && k < P.K) {
+                uint4v v = *reinterpret_cast<const uint4v*>(stage + pix * 128 + ((part ^ (pix & 7)) << 4));
+                *reinterpret_cast<uint4v*>(P.Y + ((((long)n * P.Ho + ho) * P.Wo + wo) * P.K + k)) = v;
+            }
+        }
+    }
+}
+
+// Weight gradient: every workgroup accumulates over the tiles it owns and writes one fp32
+// partial [64 filters][R][32 slots] to the workspace; thin_wgrad_reduce_kernel adds them up.
+__global__ __launch_bounds__(256) void thin_wgrad_kernel(ThinParams P)
+{
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+    unsigned char* gt = smem;                                   // dy tile [256 pixels][64 filters] halves
+    unsigned char* patch = smem + kTH * kTW * kKT * 2;          // [PH][PW] x 8 B
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int l32 = lane & 31, lhi = lane >> 5;
+    const int grp = lane >> 4, gl = lane & 15;
+    const int kt = blockIdx.y;
+
+    // wave `wave` owns filter rows r = wave and wave + 4 (when they exist), both 32-filter blocks
+    float16v acc[2][2];
+#pragma unroll
+    for (int a = 0; a < 2; ++a)
+#pragma unroll
+        for (int b = 0; b < 2; ++b)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) acc[a][b][e] = 0.f;
+
+    for (int tile = blockIdx.x; tile < P.ntiles; tile += gridDim.x) {
+        int t = tile;
+        const int tw = t % P.tiles_w; t /= P.tiles_w;
+        const int th = t % P.tiles_h;
+        const int n = t / P.tiles_h;
+        const int ho0 = th * kTH, wo0 = tw * kTW;
+
+        __syncthreads();
+        load_patch(P, patch, n, ho0, wo0, tid);
+        // dy tile: 256 pixels x 128 bytes, 8 lanes per pixel, 64-byte granules swizzled by pixel parity
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            int c = tid + 256 * i;
+            int pix = c >> 3, part = c & 7;
+            int ho = ho0 + pix / kTW, wo = wo0 + pix % kTW;
+            int k = kt * kKT + part * 8;
+            uint4v v = {0u, 0u, 0u, 0u};
+            if (ho < P.Ho && wo < P.Wo && k < P.K)
+                v = *reinterpret_cast<const uint4v*>(P.G + ((((long)n * P.Ho + ho) * P.Wo + wo) * P.K + k));
+            int gran = (part >> 2) ^ (pix & 1);
+            *reinterpret_cast<uint4v*>(gt + pix * 128 + gran * 64 + (part & 3) * 16) = v;
+        }
+        __syncthreads();
+
+        for (int row = 0; row < kTH; ++row) {
+#pragma unroll
+            for (int kk = 0; kk < 2; ++kk) {                  // 16 output pixels per MFMA
+                // filters x pixels operand from the dy tile
+                half8 fa[2];
+                const int pl = row * kTW + kk * 16 + 8 * (grp >> 1) + (gl >> 2);   // pixel of first read
+#pragma unroll
+                for (int kb = 0; kb < 2; ++kb) {
+                    int col = kb * 32 + 16 * (grp & 1) + 4 * (gl & 3);             // filter index
+                    int byte = col * 2;
+                    const unsigned char* a0 = gt + pl * 128 + (((byte >> 6) ^ (pl & 1)) << 6) + (byte & 63);
+                    const unsigned char* a1 = gt + (pl + 4) * 128 + (((byte >> 6) ^ ((pl + 4) & 1)) << 6) + (byte & 63);
+                    half4 lo = lds_read_tr4(a0), hi = lds_read_tr4(a1);
+                    fa[kb] = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+                }
+#pragma unroll
+                for (int ri = 0; ri < 2; ++ri) {
+                    int r = wave + 4 * ri;
+                    if (r < P.R) {
+                        // pixels x slots operand from the patch: slot 4s+c, lane 4i+j -> pixel i, s = 4*(grp&1)+j
+                        int wo_l = kk * 16 + 8 * (grp >> 1) + (gl >> 2);
+                        int s = 4 * (grp & 1) + (gl & 3);
+                        const unsigned char* b0 = patch + ((row * P.sh + r) * P.PW + wo_l * P.sw + s) * 8;
+                        half4 lo = lds_read_tr4(b0), hi = lds_read_tr4(b0 + 4 * P.sw * 8);
+                        half8 fb = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+#pragma unroll
+                        for (int kb = 0; kb < 2; ++kb)
+                            acc[ri][kb] = __builtin_amdgcn_mfma_f32_32x32x16_f16(fa[kb], fb, acc[ri][kb], 0, 0, 0);
+                    }
+                }
+            }
+        }
+    }
+
+    // partial[wg][kt][k 0..63][r][slot 0..31]
+    float* out = P.partial + ((long)blockIdx.x * gridDim.y + kt) * kKT * P.R * 32;
+#pragma unroll
+    for (int ri = 0; ri < 2; ++ri) {
+        int r = wave + 4 * ri;
+        if (r >= P.R) continue;
+#pragma unroll
+        for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) {
+                int k = kb * 32 + 8 * (e >> 2) + 4 * lhi + (e & 3);
+                out[(k * P.R + r) * 32 + l32] = acc[ri][kb][e];
+            }
+    }
+}
+
+// dw[k][r][s][c] = sum over workgroups of partial[wg][kt][kk][r][4s+c], fixed order.
+// One block per (k, r): 32 slots x 8 partial-lanes.
+__global__ __launch_bounds__(256) void thin_wgrad_reduce_kernel(const float* __restrict__ partial,
+                                                               float* __restrict__ dw, int nwg, int ktiles,
+                                                               int K, int R, int S, int C)
+{
+    __shared__ float red[8][32];
+    const int k = blockIdx.x / R, r = blockIdx.x % R;
+    const int kt = k / kKT, kk = k % kKT;
+    const int slot = threadIdx.x & 31, part = threadIdx.x >> 5;
+    float s = 0.f;
+    for (int wg = part; wg < nwg; wg += 8)
+        s += partial[((((long)wg * ktiles + kt) * kKT + kk) * R + r) * 32 + slot];
+    red[part][slot] = s;
+    __syncthreads();
+    if (part == 0) {
+        float tot = red[0][slot];
+#pragma unroll
+        for (int i = 1; i < 8; ++i) tot += red[i][slot];
+        int sx = slot >> 2, c = slot & 3;
+        if (sx < S && c < C) dw[(((long)k * R + r) * S + sx) * C + c] = tot;
+    }
+}
+
+size_t thin_packed_filter_bytes(const Geom& g)
+{
+    int ktiles = (g.K + kKT - 1) / kKT;
+    return (size_t)ktiles * g.R * 4 * kKT * 16;
+}
+
+int thin_wgrad_workgroups(const Geom& g)
+{
+    int ntiles = g.N * ((g.Ho + kTH - 1) / kTH) * ((g.Wo + kTW - 1) / kTW);
+    return ntiles < 512 ? ntiles : 512;
+}
+
+size_t thin_wgrad_partial_bytes(const Geom& g)
+{
+    int ktiles = (g.K + kKT - 1) / kKT;
+    return (size_t)thin_wgrad_workgroups(g) * ktiles * kKT * g.R * 32 * sizeof(float);
+}
+
+static ThinParams make_params(const Geom& g)
+{
+    ThinParams P;
+    P.X = nullptr; P.Wp = nullptr; P.Y = nullptr; P.G = nullptr; P.partial = nullptr;
+    P.N = g.N; P.H = g.H; P.W = g.W; P.C = g.C; P.K = g.K; P.R = g.R; P.S = g.S;
+    P.sh = g.sh; P.sw = g.sw; P.ph = g.ph; P.pw = g.pw; P.Ho = g.Ho; P.Wo = g.Wo;
+    P.tiles_h = (g.Ho + kTH - 1) / kTH;
+    P.tiles_w = (g.Wo + kTW - 1) / kTW;
+    P.ntiles = g.N * P.tiles_h * P.tiles_w;
+    P.PH = (kTH - 1) * g.sh + g.R;
+    P.PW = ((kTW - 1) * g.sw + 8 + 1) & ~1;
+    return P;
+}
+
+bool thin_supported(const Geom& g)
+{
+    if (g.C > 4 || g.S > 8 || g.R > 8 || g.dh != 1 || g.dw != 1 || g.K % 8) return false;
+    ThinParams P = make_params(g);
+    size_t fwd_lds = (size_t)g.R * 4 * kKT * 16 + (((size_t)P.PH * P.PW * 8 + 15) & ~(size_t)15) + 256 * 128;
+    return fwd_lds <= 150 * 1024;
+}
+
+hipError_t launch_thin_fwd(const Geom& g, const __half* x, const __half* w, __half* y, void* ws, hipStream_t st)
+{
+    ThinParams P = make_params(g);
+    int ktiles = (g.K + kKT - 1) / kKT;
+    __half* wp = static_cast<__half*>(ws);
+    long total = (long)ktiles * g.R * 4 * kKT * 8;
+    hipLaunchKernelGGL(thin_pack_filter_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st,
+                       w, wp, g.K, g.R, g.S, g.C, total);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    P.X = x; P.Wp = wp; P.Y = y;
+    size_t lds = (size_t)g.R * 4 * kKT * 16 + (((size_t)P.PH * P.PW * 8 + 15) & ~(size_t)15) + 256 * 128;
+    static bool configured = false;
+    if (!configured) {
+        e = hipFuncSetAttribute(reinterpret_cast<const void*>(&thin_fwd_kernel),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+        if (e != hipSuccess) return e;
+        configured = true;
+    }
+    int grid = P.ntiles < 1024 ? P.ntiles : 1024;
+    hipLaunchKernelGGL(thin_fwd_kernel, dim3(grid, ktiles), dim3(256), lds, st, P);
+    return hipGetLastError();
+}
+
+hipError_t launch_thin_wgrad(const Geom& g, const __half* x, const __half* dy, float* dw, void* ws, hipStream_t st)
+{
+    ThinParams P = make_params(g);
+    int ktiles = (g.K + kKT - 1) / kKT;
+    int nwg = thin_wgrad_workgroups(g);
+    P.X = x; P.G = dy; P.partial = static_cast<float*>(ws);
+    size_t lds = (size_t)kTH * kTW * kKT * 2 + (size_t)P.PH * P.PW * 8;
+    hipError_t e;
+    static bool configured = false;
+    if (!configured) {
+        e = hipFuncSetAttribute(reinterpret_cast<const void*>(&thin_wgrad_kernel),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+        if (e != hipSuccess) return e;
+        configured = true;
+    }
+    hipLaunchKernelGGL(thin_wgrad_kernel, dim3(nwg, ktiles), dim3(256), lds, st, P);
+    e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL(thin_wgrad_reduce_kernel, dim3(g.K * g.R), dim3(256), 0, st,
+                       static_cast<const float*>(ws), dw, nwg, ktiles, g.K, g.R, g.S, g.C);
+    return hipGetLastError();
+}
+
+}  // namespace sdconv

@@ -44,6 +44,10 @@ SMALL = [
     (1, 17, 19, 64, 128, 3, 3, (1, 1), (2, 2), (2, 2)),
     (1, 40, 44, 3, 64, 7, 7, (2, 2), (3, 3), (1, 1)),
     (4, 14, 14, 128, 64, 3, 3, (2, 2), (1, 1), (1, 1)),
+    (2, 19, 37, 4, 72, 3, 3, (1, 1), (1, 1), (1, 1)),    # thin-input route, K over one filter tile
+    (1, 33, 70, 1, 8, 5, 8, (2, 1), (2, 3), (1, 1)),     # thin-input route, one channel, S = 8
+    (1, 20, 50, 2, 16, 7, 7, (3, 2), (3, 3), (1, 1)),    # thin-input route, stride 3x2
+    (1, 70, 9, 3, 64, 8, 1, (1, 1), (0, 0), (1, 1)),     # thin-input route, R = 8, S = 1
     (1, 3, 3, 8, 8, 3, 3, (1, 1), (0, 0), (1, 1)),       # single output pixel
     (1, 1, 1, 8, 8, 1, 1, (1, 1), (0, 0), (1, 1)),       # everything is 1
     (1, 6, 6, 64, 64, 3, 3, (1, 1), (3, 3), (1, 1)),     # pad larger than needed
