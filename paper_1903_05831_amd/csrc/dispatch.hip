@@ -20,14 +20,30 @@ static bool force_direct()
     return v == 1;
 }
 
-static int forced_variant()
-{
-    static int v = -2;
-    if (v == -2) v = env_int("SDCONV_IGEMM_VARIANT", -1);
-    return v;
-}
+// Tuning hooks, read on every call so that a tuner can switch them between launches.
+static int forced_variant() { return env_int("SDCONV_IGEMM_VARIANT", -1); }
+static int forced_wgrad_splits() { return env_int("SDCONV_WGRAD_SPLITS", -1); }
 
 static size_t align256(size_t b) { return (b + 255) & ~(size_t)255; }
+
+// Measured choices for known geometries (written by tune.py on the target GPU); anything not
+// listed falls back to the heuristics below.
+struct TunedEntry { int N, H, W, C, K, R, S, sh, sw, ph, pw, dh, dw, pass, variant, splits; };
+static const TunedEntry kTuned[] = {
+#include "tuned_table.inc"
+    {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, -1, 0, 0},
+};
+
+static const TunedEntry* tuned_lookup(const Geom& g, int pass)
+{
+    if (env_int("SDCONV_NO_TUNED_TABLE", 0)) return nullptr;
+    for (const TunedEntry* e = kTuned; e->pass >= 0; ++e)
+        if (e->pass == pass && e->N == g.N && e->H == g.H && e->W == g.W && e->C == g.C && e->K == g.K &&
+            e->R == g.R && e->S == g.S && e->sh == g.sh && e->sw == g.sw && e->ph == g.ph && e->pw == g.pw &&
+            e->dh == g.dh && e->dw == g.dw)
+            return e;
+    return nullptr;
+}
 
 // The MFMA route moves 16-byte (8-half) vectors along the channel axis of every tensor.
 static bool igemm_ok(const Geom& g)
@@ -63,21 +79,26 @@ static int row_tiles(const Geom& g, bool dgrad, int bm, int* starts, int* nclass
     return acc;
 }
 
+static const IgemmVariant& igemm_variant(int v)
+{
+    return v >= 100 ? kIgemmDmaVariants[v - 100] : kIgemmVariants[v];
+}
+
 static int pick_variant(const Geom& g, bool dgrad)
 {
     int fv = forced_variant();
     if (fv >= 0 && fv < kNumIgemmVariants) return fv;
+    if (fv >= 100 && fv < 100 + kNumIgemmDmaVariants) return fv;
+    if (const TunedEntry* e = tuned_lookup(g, dgrad ? SDCONV_DGRAD : SDCONV_FWD)) return e->variant;
     int nout = dgrad ? g.C : g.K;
-    // Narrow filters: a 64-wide tile wastes nothing; otherwise 128 columns.  Prefer the
-    // taller tile when it still yields at least two workgroups per compute unit.
+    int kgemm = g.R * g.S * (dgrad ? g.K : g.C);
     int starts[kMaxClasses + 1], nc;
-    if (nout <= 64) {
-        int t = row_tiles(g, dgrad, 256, starts, &nc);
-        return (t >= 512) ? 2 : 3;
-    }
-    int tn = (nout + 127) / 128;
-    int t = row_tiles(g, dgrad, 256, starts, &nc) * tn;
-    return (t >= 512) ? 1 : 0;
+    // Narrow outputs: 64-wide tiles.  Long contractions with enough rows to fill the chip
+    // with 256x256 tiles: the big tile (half the LDS traffic per flop).  Otherwise 128x128.
+    if (nout <= 64) return 100 + 7;
+    int t256 = row_tiles(g, dgrad, 256, starts, &nc) * ((nout + 255) / 256);
+    if (kgemm >= 2048 && t256 >= 160) return 100 + 8;
+    return 100 + 0;
 }
 
 static bool thin_ok(const Geom& g) { return !force_direct() && g.C <= 4 && thin_supported(g); }
@@ -87,15 +108,18 @@ Plan plan_fwd(const Geom& g)
     if (thin_ok(g)) return Plan{ROUTE_THIN, 0, 1, align256(thin_packed_filter_bytes(g)), "thin_fwd"};
     if (!igemm_ok(g)) return Plan{ROUTE_DIRECT, 0, 1, 0, "direct_fwd"};
     int v = pick_variant(g, false);
-    return Plan{ROUTE_IGEMM, v, 1, 0, kIgemmVariants[v].fwd_name};
+    return Plan{ROUTE_IGEMM, v, 1, 0, igemm_variant(v).fwd_name};
 }
 
 Plan plan_dgrad(const Geom& g)
 {
+    if (!force_direct() && g.C <= 4 && g.K % 8 == 0 && g.sh * g.sw <= kMaxClasses &&
+        thin_dgrad_lds_bytes(g) <= 64 * 1024)
+        return Plan{ROUTE_THIN, 0, 1, align256((size_t)g.K * g.R * g.S * g.C * sizeof(__half)), "thin_dgrad"};
     if (!igemm_ok(g) || g.sh * g.sw > kMaxClasses) return Plan{ROUTE_DIRECT, 0, 1, 0, "direct_dgrad"};
     int v = pick_variant(g, true);
     size_t ws = align256((size_t)g.K * g.R * g.S * g.C * sizeof(__half));
-    return Plan{ROUTE_IGEMM, v, 1, ws, kIgemmVariants[v].dgrad_name};
+    return Plan{ROUTE_IGEMM, v, 1, ws, igemm_variant(v).dgrad_name};
 }
 
 // Pixel-range count for the weight gradient: enough workgroups to fill the chip a few times
@@ -106,8 +130,10 @@ static void wgrad_split(const Geom& g, int variant, int* splits, int* steps_per_
     long tiles = (long)((g.K + v.bm - 1) / v.bm) * ((g.C + v.bn - 1) / v.bn) * g.R * g.S;
     long P = (long)g.N * g.Ho * g.Wo;
     long total_steps = (P + 63) / 64;
-    static int target = env_int("SDCONV_WGRAD_TARGET_BLOCKS", 768);
-    long want = (target + tiles - 1) / tiles;
+    long want = (384 + tiles - 1) / tiles;
+    if (const TunedEntry* e = tuned_lookup(g, SDCONV_WGRAD)) want = e->splits;
+    int fs = forced_wgrad_splits();
+    if (fs > 0) want = fs;
     long cap = total_steps / 4;
     if (cap < 1) cap = 1;
     if (want > cap) want = cap;
@@ -140,11 +166,13 @@ static hipError_t run_igemm(const Geom& g, const Plan& p, bool dgrad, const __ha
     P.sh = g.sh; P.sw = g.sw; P.ph = g.ph; P.pw = g.pw; P.dh = g.dh; P.dw = g.dw;
     P.mode = dgrad ? 1 : 0;
     P.sw_cls = dgrad ? g.sw : 1;
-    const IgemmVariant& v = kIgemmVariants[p.variant];
+    const IgemmVariant& v = igemm_variant(p.variant);
     int tiles_m = row_tiles(g, dgrad, v.bm, P.class_tile_start, &P.nclasses);
     P.tiles_n = (P.Cd + v.bn - 1) / v.bn;
+    P.total_tiles = tiles_m * P.tiles_n;
     P.b_row_pitch = g.R * g.S * P.Cs;
-    return launch_igemm(p.variant, P, tiles_m * P.tiles_n, st);
+    if (p.variant >= 100) return launch_igemm_dma(p.variant - 100, P, st);
+    return launch_igemm(p.variant, P, P.total_tiles, st);
 }
 
 hipError_t run_fwd(const Geom& g, const Plan& p, const __half* x, const __half* w, __half* y, void* ws, hipStream_t st)
@@ -160,6 +188,7 @@ hipError_t run_dgrad(const Geom& g, const Plan& p, const __half* dy, const __hal
     __half* wT = static_cast<__half*>(ws);
     hipError_t e = launch_filter_transpose(w, wT, g.K, g.R * g.S, g.C, st);
     if (e != hipSuccess) return e;
+    if (p.route == ROUTE_THIN) return launch_thin_dgrad(g, dy, wT, dx, st);
     return run_igemm(g, p, true, dy, wT, dx, st);
 }
 

@@ -20,6 +20,7 @@ struct IgemmParams {
     int nclasses;      // 1, or stride_h*stride_w for a data gradient
     int sw_cls;        // classes along w (stride_w for a data gradient, else 1)
     int tiles_n;       // column tiles
+    int total_tiles;   // row tiles (all classes) x column tiles
     int b_row_pitch;   // R*S*Cs
     int class_tile_start[kMaxClasses + 1];   // first row-tile of each class, then the total
 };
@@ -28,6 +29,9 @@ struct IgemmVariant { int bm, bn; const char* fwd_name; const char* dgrad_name; 
 constexpr int kNumIgemmVariants = 4;
 extern const IgemmVariant kIgemmVariants[kNumIgemmVariants];
 
+constexpr int kNumIgemmDmaVariants = 12;
+extern const IgemmVariant kIgemmDmaVariants[kNumIgemmDmaVariants];
+hipError_t launch_igemm_dma(int variant, const IgemmParams& P, hipStream_t st);
 hipError_t launch_igemm(int variant, const IgemmParams& P, int total_tiles, hipStream_t st);
 hipError_t launch_filter_transpose(const __half* w, __half* wT, int K, int RS, int C, hipStream_t st);
 

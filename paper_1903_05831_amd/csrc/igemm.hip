@@ -95,7 +95,7 @@ __global__ __launch_bounds__(kThreads) void igemm_kernel(IgemmParams P)
         if (lane == 0) tap_cnt[0] = __popcll(mask);
     }
     __syncthreads();
-    const int ntaps = tap_cnt[0];
+    const int ntaps = __builtin_amdgcn_readfirstlane(tap_cnt[0]);
     const int kchunks = (P.Cs + kBK - 1) / kBK;
     const int nk = ntaps * kchunks;
 

@@ -16,7 +16,19 @@ struct ThinParams {
     int PH, PW;                     // LDS patch extent in padded pixels
 };
 
+struct ThinDgradParams {
+    const __half* G;     // upstream gradient [N][Ho][Wo][K]
+    const __half* WT;    // filter as [C][R][S][K]
+    __half* DX;          // [N][H][W][C]
+    int N, H, W, C, K, R, S;
+    int sh, sw, ph, pw, dh, dw, Ho, Wo;
+    int nclasses;
+    int class_block_start[17];
+};
+
 bool thin_supported(const Geom& g);
+size_t thin_dgrad_lds_bytes(const Geom& g);
+hipError_t launch_thin_dgrad(const Geom& g, const __half* dy, const __half* wT, __half* dx, hipStream_t st);
 size_t thin_packed_filter_bytes(const Geom& g);
 size_t thin_wgrad_partial_bytes(const Geom& g);
 hipError_t launch_thin_fwd(const Geom& g, const __half* x, const __half* w, __half* y, void* ws, hipStream_t st);

@@ -290,6 +290,112 @@ __global__ __launch_bounds__(256) void thin_wgrad_reduce_kernel(const float* __r
     }
 }
 
+// Data gradient for C <= 4 on the vector ALU (v_dot2_f32_f16): the output has too few
+// channels for a matrix tile.  One lane per dx pixel, lanes of a wave walk along w inside one
+// stride-parity class, so the taps are wave-uniform and a wave reads 64 consecutive dy pixels
+// (whole 128-byte lines) per tap.  The filter, re-laid-out as WT[C][R][S][K], sits in LDS and
+// is read with uniform (broadcast) addresses.  KC = 16-byte chunks of K handled per inner step.
+template <int KC>
+__global__ __launch_bounds__(256) void thin_dgrad_kernel(ThinDgradParams P)
+{
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+    const int RS = P.R * P.S;
+    {
+        const uint4v* src = reinterpret_cast<const uint4v*>(P.WT);
+        const int chunks = P.C * RS * P.K / 8;
+        for (int i = threadIdx.x; i < chunks; i += 256) reinterpret_cast<uint4v*>(smem)[i] = src[i];
+    }
+    __syncthreads();
+    const half8* wlds = reinterpret_cast<const half8*>(smem);
+
+    int blk = blockIdx.x, cls = 0;
+    while (cls + 1 < P.nclasses && blk >= P.class_block_start[cls + 1]) ++cls;
+    blk -= P.class_block_start[cls];
+    const int ca = cls / P.sw, cb = cls % P.sw;
+    const int Hi = (P.H - ca + P.sh - 1) / P.sh, Wj = (P.W - cb + P.sw - 1) / P.sw;
+    const int Mc = P.N * Hi * Wj;
+    const int m = blk * 256 + threadIdx.x;
+    const bool live = m < Mc;
+    int n = 0, i = 0, j = 0;
+    if (live) {
+        n = m / (Hi * Wj);
+        int rem = m - n * (Hi * Wj);
+        i = rem / Wj;
+        j = rem - i * Wj;
+    }
+    float acc[4] = {0.f, 0.f, 0.f, 0.f};
+    const int kchunks = P.K / 8;
+    for (int r = 0; r < P.R; ++r) {
+        const int th = ca + P.ph - r * P.dh;
+        if (th % P.sh) continue;
+        const int ho = i + th / P.sh;
+        for (int s = 0; s < P.S; ++s) {
+            const int tw = cb + P.pw - s * P.dw;
+            if (tw % P.sw) continue;
+            const int wo = j + tw / P.sw;
+            const bool ok = live && (unsigned)ho < (unsigned)P.Ho && (unsigned)wo < (unsigned)P.Wo;
+            const half8* gp = reinterpret_cast<const half8*>(P.G + (((long)n * P.Ho + ho) * P.Wo + wo) * P.K);
+            const int tap = r * P.S + s;
+            for (int kc0 = 0; kc0 < kchunks; kc0 += KC) {
+                half8 g[KC];
+#pragma unroll
+                for (int u = 0; u < KC; ++u) {
+                    half8 z = {0, 0, 0, 0, 0, 0, 0, 0};
+                    g[u] = z;
+                    if (ok) g[u] = gp[kc0 + u];
+                }
+#pragma unroll
+                for (int c = 0; c < 4; ++c) {
+                    if (c < P.C) {
+                        const half8* wp = wlds + ((c * RS + tap) * kchunks + kc0);
+                        float a = acc[c];
+#pragma unroll
+                        for (int u = 0; u < KC; ++u) {
+                            const half8 wv = wp[u];
+                            a = __builtin_amdgcn_fdot2(g[u].s01, wv.s01, a, false);
+                            a = __builtin_amdgcn_fdot2(g[u].s23, wv.s23, a, false);
+                            a = __builtin_amdgcn_fdot2(g[u].s45, wv.s45, a, false);
+                            a = __builtin_amdgcn_fdot2(g[u].s67, wv.s67, a, false);
+                        }
+                        acc[c] = a;
+                    }
+                }
+            }
+        }
+    }
+    if (live) {
+        __half* out = P.DX + (((long)n * P.H + (ca + P.sh * i)) * P.W + (cb + P.sw * j)) * P.C;
+#pragma unroll
+        for (int c = 0; c < 4; ++c)
+            if (c < P.C) out[c] = __float2half_rn(acc[c]);
+    }
+}
+
+size_t thin_dgrad_lds_bytes(const Geom& g) { return (size_t)g.C * g.R * g.S * g.K * 2; }
+
+hipError_t launch_thin_dgrad(const Geom& g, const __half* dy, const __half* wT, __half* dx, hipStream_t st)
+{
+    ThinDgradParams P;
+    P.G = dy; P.WT = wT; P.DX = dx;
+    P.N = g.N; P.H = g.H; P.W = g.W; P.C = g.C; P.K = g.K; P.R = g.R; P.S = g.S;
+    P.sh = g.sh; P.sw = g.sw; P.ph = g.ph; P.pw = g.pw; P.dh = g.dh; P.dw = g.dw; P.Ho = g.Ho; P.Wo = g.Wo;
+    P.nclasses = g.sh * g.sw;
+    int acc = 0;
+    for (int q = 0; q < P.nclasses; ++q) {
+        int a = q / g.sw, b = q % g.sw;
+        long Hi = (g.H - a + g.sh - 1) / g.sh, Wj = (g.W - b + g.sw - 1) / g.sw;
+        if (Hi < 0) Hi = 0;
+        if (Wj < 0) Wj = 0;
+        P.class_block_start[q] = acc;
+        acc += (int)(((long)g.N * Hi * Wj + 255) / 256);
+    }
+    P.class_block_start[P.nclasses] = acc;
+    size_t lds = thin_dgrad_lds_bytes(g);
+    if (g.K % 64 == 0) hipLaunchKernelGGL(thin_dgrad_kernel<8>, dim3(acc), dim3(256), lds, st, P);
+    else hipLaunchKernelGGL(thin_dgrad_kernel<1>, dim3(acc), dim3(256), lds, st, P);
+    return hipGetLastError();
+}
+
 size_t thin_packed_filter_bytes(const Geom& g)
 {
     int ktiles = (g.K + kKT - 1) / kKT;

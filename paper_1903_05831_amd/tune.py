@@ -1,0 +1,106 @@
+"""Measures every kernel variant on every distinct layer of the benchmark workloads on the
+GPU at hand and writes the winners to csrc/tuned_table.inc (rebuild the library afterwards).
+
+    python -m paper_1903_05831_amd.tune [--configs 5] [--ms 10]
+
+The dispatcher reads SDCONV_IGEMM_VARIANT / SDCONV_WGRAD_SPLITS on every call, which is how
+this script forces a variant.  Unlisted geometries keep using the built-in heuristics.
+"""
+from __future__ import annotations
+
+import argparse
+import os
+import sys
+
+import torch
+
+import paper_1903_05831_amd as sd
+from paper_1903_05831_amd import workloads
+
+FWD_DGRAD_VARIANTS = [100, 101, 102, 104, 105, 106, 107, 108, 109]
+WGRAD_SPLITS = [1, 2, 3, 4, 6, 8, 12, 16, 24, 32, 48, 64, 96, 128, 192, 256, 384]
+HERE = os.path.dirname(os.path.abspath(__file__))
+
+
+def time_call(fn, ms_budget: float) -> float:
+    for _ in range(2):
+        fn()
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record(); fn(); e1.record(); torch.cuda.synchronize()
+    t1 = max(e0.elapsed_time(e1), 1e-3)
+    iters = max(3, min(500, int(ms_budget / t1)))
+    best = 1e30
+    for _ in range(2):
+        e0.record()
+        for _ in range(iters):
+            fn()
+        e1.record(); torch.cuda.synchronize()
+        best = min(best, e0.elapsed_time(e1) / iters)
+    return best
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--configs", type=str, default="1,2,3,4,5")
+    ap.add_argument("--ms", type=float, default=8.0)
+    ap.add_argument("--out", type=str, default=os.path.join(HERE, "csrc", "tuned_table.inc"))
+    args = ap.parse_args()
+    dev = torch.device("cuda:0")
+    st = torch.cuda.current_stream().cuda_stream
+    os.environ["SDCONV_NO_TUNED_TABLE"] = "1"
+    seen = set()
+    lines = []
+    for cfg in [int(c) for c in args.configs.split(",")]:
+        for l in workloads.CONFIGS[cfg]:
+            key = (l.N, l.H, l.W, l.C, l.K, l.R, l.S, l.stride, l.pad, l.dil)
+            if key in seen or l.C % 8 or l.K % 8:
+                continue
+            seen.add(key)
+            d = sd.desc_of(l)
+            x = torch.randn(l.x_shape, device=dev, dtype=torch.float16)
+            w = torch.randn(l.w_shape, device=dev, dtype=torch.float16) * 0.05
+            g = torch.randn(l.y_shape, device=dev, dtype=torch.float16)
+            y = torch.empty(l.y_shape, device=dev, dtype=torch.float16)
+            dx = torch.empty(l.x_shape, device=dev, dtype=torch.float16)
+            dw = torch.empty(l.w_shape, device=dev, dtype=torch.float32)
+            geom = f"{l.N},{l.H},{l.W},{l.C},{l.K},{l.R},{l.S},{l.stride},{l.stride},{l.pad},{l.pad},{l.dil},{l.dil}"
+            for pid, pname in ((sd.FWD, "fwd"), (sd.DGRAD, "dgrad")):
+                results = []
+                for v in FWD_DGRAD_VARIANTS:
+                    os.environ["SDCONV_IGEMM_VARIANT"] = str(v)
+                    ws = torch.empty(max(sd.conv2d_workspace_bytes(d, pid), 256), dtype=torch.uint8, device=dev)
+                    if pid == sd.FWD:
+                        fn = lambda: sd.conv2d_fwd(d, x, w, y, ws, st)
+                    else:
+                        fn = lambda: sd.conv2d_dgrad(d, g, w, dx, ws, st)
+                    results.append((time_call(fn, args.ms), v))
+                os.environ.pop("SDCONV_IGEMM_VARIANT")
+                t, v = min(results)
+                print(f"{l.name:9s} {pname:5s} best variant {v} {t*1e3:8.1f} us {l.flops/t/1e9:7.1f} TF/s   "
+                      + " ".join(f"{vv}:{tt*1e3:.0f}" for tt, vv in results), flush=True)
+                lines.append(f"    {{{geom}, {pid}, {v}, 0}},  // {l.name} {pname} {t*1e3:.1f} us")
+            results = []
+            for sp in WGRAD_SPLITS:
+                os.environ["SDCONV_WGRAD_SPLITS"] = str(sp)
+                ws = torch.empty(max(sd.conv2d_workspace_bytes(d, sd.WGRAD), 256), dtype=torch.uint8, device=dev)
+                if ws.numel() > (2 << 30):
+                    continue
+                results.append((time_call(lambda: sd.conv2d_wgrad(d, x, g, dw, ws, st), args.ms), sp))
+            os.environ.pop("SDCONV_WGRAD_SPLITS")
+            t, sp = min(results)
+            print(f"{l.name:9s} wgrad best splits {sp} {t*1e3:8.1f} us {l.flops/t/1e9:7.1f} TF/s   "
+                  + " ".join(f"{ss}:{tt*1e3:.0f}" for tt, ss in results), flush=True)
+            lines.append(f"    {{{geom}, {sd.WGRAD}, 0, {sp}}},  // {l.name} wgrad {t*1e3:.1f} us")
+            del x, w, g, y, dx, dw
+            torch.cuda.empty_cache()
+    with open(args.out, "w") as f:
+        f.write("// Written by tune.py on %s: {N,H,W,C,K,R,S,sh,sw,ph,pw,dh,dw, pass, variant, splits}\n"
+                % torch.cuda.get_device_name(0))
+        f.write("\n".join(lines) + "\n")
+    print("wrote", args.out, len(lines), "entries")
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())
