@@ -192,10 +192,12 @@ __global__ __launch_bounds__(64 * WGM * WGN) void igemm_dma_kernel(IgemmParams P
             unsigned voff = cok ? b_off[p] : kOutOfRange;
             dma16(voff, rsrcB, bo + cbytes, sbase + BM * ROWB + p * RPP * ROWB);
         }
-        int kc1 = nx_kc + 1;
-        bool wrap = kc1 == kchunks;
-        nx_kc = __builtin_amdgcn_readfirstlane(wrap ? 0 : kc1);
-        nx_tap = __builtin_amdgcn_readfirstlane(wrap ? nx_tap + 1 : nx_tap);
+        // taps vary fastest: the 9 taps of a 3x3 re-read nearly the same pixels of one
+        // 64-channel slab back to back, while it is still in L2
+        int t1 = nx_tap + 1;
+        bool wrap = t1 == ntaps;
+        nx_tap = __builtin_amdgcn_readfirstlane(wrap ? 0 : t1);
+        nx_kc = __builtin_amdgcn_readfirstlane(wrap ? nx_kc + 1 : nx_kc);
     };
 
     float16v acc[FN][FM];
