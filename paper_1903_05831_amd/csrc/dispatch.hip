@@ -23,6 +23,7 @@ static bool force_direct()
 // Tuning hooks, read on every call so that a tuner can switch them between launches.
 static int forced_variant() { return env_int("SDCONV_IGEMM_VARIANT", -1); }
 static int forced_wgrad_splits() { return env_int("SDCONV_WGRAD_SPLITS", -1); }
+static int forced_wgrad_variant() { return env_int("SDCONV_WGRAD_VARIANT", -1); }
 
 static size_t align256(size_t b) { return (b + 255) & ~(size_t)255; }
 
@@ -124,9 +125,22 @@ Plan plan_dgrad(const Geom& g)
 
 // Pixel-range count for the weight gradient: enough workgroups to fill the chip a few times
 // over, but at least four 64-pixel steps per range.
+static const WgradVariant& wgrad_variant(int v)
+{
+    return v >= 100 ? kWgradDmaVariants[v - 100] : kWgradVariants[v];
+}
+
+static int pick_wgrad_variant(const Geom& g)
+{
+    int fv = forced_wgrad_variant();
+    if ((fv >= 0 && fv < kNumWgradVariants) || (fv >= 100 && fv < 100 + kNumWgradDmaVariants)) return fv;
+    if (const TunedEntry* e = tuned_lookup(g, SDCONV_WGRAD)) return e->variant;
+    return (g.K <= 64) ? 1 : 0;
+}
+
 static void wgrad_split(const Geom& g, int variant, int* splits, int* steps_per_split)
 {
-    const WgradVariant& v = kWgradVariants[variant];
+    const WgradVariant& v = wgrad_variant(variant);
     long tiles = (long)((g.K + v.bm - 1) / v.bm) * ((g.C + v.bn - 1) / v.bn) * g.R * g.S;
     long P = (long)g.N * g.Ho * g.Wo;
     long total_steps = (P + 63) / 64;
@@ -147,11 +161,11 @@ Plan plan_wgrad(const Geom& g)
 {
     if (thin_ok(g)) return Plan{ROUTE_THIN, 0, 1, align256(thin_wgrad_partial_bytes(g)), "thin_wgrad"};
     if (!igemm_ok(g)) return Plan{ROUTE_DIRECT, 0, 1, 0, "direct_wgrad"};
-    int v = (g.K <= 64) ? 1 : 0;
+    int v = pick_wgrad_variant(g);
     int splits, sps;
     wgrad_split(g, v, &splits, &sps);
     size_t ws = splits > 1 ? align256((size_t)splits * g.K * g.R * g.S * g.C * sizeof(float)) : 0;
-    return Plan{ROUTE_IGEMM, v, splits, ws, kWgradVariants[v].name};
+    return Plan{ROUTE_IGEMM, v, splits, ws, wgrad_variant(v).name};
 }
 
 static hipError_t run_igemm(const Geom& g, const Plan& p, bool dgrad, const __half* A, const __half* B,
@@ -196,7 +210,7 @@ hipError_t run_wgrad(const Geom& g, const Plan& p, const __half* x, const __half
 {
     if (p.route == ROUTE_DIRECT) return launch_direct_wgrad(g, x, dy, dw, st);
     if (p.route == ROUTE_THIN) return launch_thin_wgrad(g, x, dy, dw, ws, st);
-    const WgradVariant& v = kWgradVariants[p.variant];
+    const WgradVariant& v = wgrad_variant(p.variant);
     WgradParams P;
     P.X = x; P.G = dy;
     P.N = g.N; P.H = g.H; P.W = g.W; P.C = g.C; P.K = g.K; P.R = g.R; P.S = g.S;
@@ -207,7 +221,7 @@ hipError_t run_wgrad(const Geom& g, const Plan& p, const __half* x, const __half
     P.tiles_k = (g.K + v.bm - 1) / v.bm;
     P.tiles_c = (g.C + v.bn - 1) / v.bn;
     P.out = (P.splits > 1) ? static_cast<float*>(ws) : dw;
-    hipError_t e = launch_wgrad(p.variant, P, st);
+    hipError_t e = p.variant >= 100 ? launch_wgrad_dma(p.variant - 100, P, st) : launch_wgrad(p.variant, P, st);
     if (e != hipSuccess || P.splits == 1) return e;
     return launch_splitk_reduce(static_cast<const float*>(ws), dw, P.splits, (long)g.K * g.R * g.S * g.C, st);
 }

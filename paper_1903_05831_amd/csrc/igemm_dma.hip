@@ -22,42 +22,13 @@
 // of LDS and would drain the whole ring before each fragment read.
 #include "common.h"
 #include "igemm.h"
+#include "dma.h"
 
 namespace sdconv {
 
 typedef _Float16 half8 __attribute__((ext_vector_type(8)));
 typedef _Float16 half4 __attribute__((ext_vector_type(4)));
 typedef float float16v __attribute__((ext_vector_type(16)));
-
-typedef int int4v __attribute__((ext_vector_type(4)));
-
-constexpr unsigned kOutOfRange = 0x80000000u;   // byte offset no tensor here reaches
-
-// Raw buffer descriptor over `bytes` bytes at `p` (stride 0, range-checked on the offset).
-__device__ __forceinline__ int4v make_rsrc(const void* p, unsigned bytes)
-{
-    unsigned long long a = reinterpret_cast<unsigned long long>(p);
-    int4v r;
-    r.x = (int)(unsigned)a;
-    r.y = (int)((a >> 32) & 0xffffu);
-    r.z = (int)bytes;
-    r.w = 0x00020000;
-    return r;
-}
-
-// 16 bytes per lane from buffer offset voff + soff to LDS address lds_base + lane*16
-// (rsrc, soff, lds_base wave-uniform).  Offsets at or past the descriptor's size yield zeros.
-__device__ __forceinline__ void dma16(unsigned voff, int4v rsrc, unsigned soff, unsigned lds_base)
-{
-    asm volatile("s_mov_b32 m0, %3\n\ts_nop 0\n\tbuffer_load_dwordx4 %0, %1, %2 offen lds"
-                 :: "v"(voff), "s"(rsrc), "s"(soff), "s"(lds_base) : "memory");
-}
-
-template <int N>
-__device__ __forceinline__ void wait_vmcnt()
-{
-    asm volatile("s_waitcnt vmcnt(%0)" :: "n"(N) : "memory");
-}
 
 // BK = contraction halves per stage (64 or 32): a tile row is BK*2 bytes = CPR 16-byte chunks.
 template <int MODE, int BM, int BN, int WGM, int WGN, int S, int BK>

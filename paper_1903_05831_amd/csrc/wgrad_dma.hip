@@ -1,0 +1,293 @@
+// Weight gradient with an asynchronous global->LDS pipeline (see wgrad.hip for the maths).
+//
+//   dw[k][r][s][c] = sum_p dy[p][k] * x[src(p; r,s)][c],   p = (n,ho,wo)
+//
+// One workgroup owns a (filter tile, channel tile, tap, pixel range).  Per contraction step
+// it needs BP pixels of dy (rows of BM filters) and the BP matching pixels of x (rows of BN
+// channels); both tiles go to LDS as they sit in memory, [pixel][channel], with
+// buffer_load_dwordx4 ... lds into a ring of S stages, and the MFMA fragments come from the
+// transposing LDS read (four consecutive pixels of one channel per lane).
+//
+// Addressing: dy rows are consecutive pixels, so a lane's offset is fixed and the buffer
+// descriptor's base moves by BP rows per step; its shrinking size makes the hardware range
+// check zero the rows past the last pixel.  x rows are gathered: BP lanes decode one pixel
+// each per step into an LDS table of byte offsets (out-of-image -> out of range -> zeros), one
+// step ahead of the loads that use it; with a 1x1 stride-1 unpadded filter x is addressed like
+// dy and the table is skipped (LINEAR).
+//
+// 64-byte granules of a tile row are XOR-swizzled with the row number (applied on the global
+// side by choosing which chunk a lane fetches) so the transposing reads are conflict-free.
+#include "common.h"
+#include "wgrad.h"
+#include "dma.h"
+
+namespace sdconv {
+
+typedef _Float16 half8 __attribute__((ext_vector_type(8)));
+typedef _Float16 half4 __attribute__((ext_vector_type(4)));
+typedef short short4v __attribute__((ext_vector_type(4)));
+typedef float float16v __attribute__((ext_vector_type(16)));
+
+__device__ __forceinline__ half4 lds_read_tr16(const unsigned char* p)
+{
+    typedef __attribute__((address_space(3))) short4v* lds_ptr;
+    short4v v = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr)(p));
+    return __builtin_bit_cast(half4, v);
+}
+
+// Byte offset of (row, col half-index) in a [rows][BW halves] tile with swizzled granules.
+template <int BW>
+__device__ __forceinline__ int sw_off(int row, int col)
+{
+    constexpr int pitch = BW * 2;
+    constexpr int gmask = (pitch >= 256) ? 3 : (pitch / 64 - 1);
+    int byte = col * 2;
+    int gran = (byte >> 6) ^ (row & gmask);
+    return row * pitch + (gran << 6) + (byte & 63);
+}
+
+template <int BM, int BN, int WGM, int WGN, int S, int BP, bool LINEAR>
+__global__ __launch_bounds__(64 * WGM * WGN) void wgrad_dma_kernel(WgradParams P)
+{
+    constexpr int NW = WGM * WGN, NT = 64 * NW;
+    constexpr int WM = BM / WGM, WN = BN / WGN;
+    constexpr int FM = WM / 32, FN = WN / 32;
+    constexpr int CRG = BM / 8, CRX = BN / 8;           // 16-byte chunks per tile row
+    constexpr int RPG = NT / CRG, RPX = NT / CRX;       // rows one pass of all threads covers
+    constexpr int PG = BP / RPG, PX = BP / RPX;         // DMA loads per thread and stage
+    constexpr int GBYTES = BP * BM * 2, XBYTES = BP * BN * 2, STAGE = GBYTES + XBYTES;
+    constexpr int INFLIGHT = (S - 2) * (PG + PX);
+    constexpr int GMG = (BM * 2 >= 256) ? 3 : (BM * 2 / 64 - 1);
+    constexpr int GMX = (BN * 2 >= 256) ? 3 : (BN * 2 / 64 - 1);
+    static_assert(WM % 32 == 0 && WN % 32 == 0, "wave tile");
+    static_assert(PG >= 1 && PX >= 1 && BP % RPG == 0 && BP % RPX == 0 && RPG % 4 == 0 && RPX % 4 == 0, "staging");
+    static_assert(S >= 2 && INFLIGHT < 64 && BP % 16 == 0 && BP <= NT, "pipeline");
+
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+    const unsigned lds0 = (unsigned)(size_t)(__attribute__((address_space(3))) unsigned char*)smem;
+    unsigned* xtab = reinterpret_cast<unsigned*>(smem + S * STAGE);     // [S][BP] byte offsets of x pixels
+
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wm = wave / WGN, wn = wave % WGN;
+
+    int b = blockIdx.x;
+    const int tc = b % P.tiles_c; b /= P.tiles_c;
+    const int tk = b % P.tiles_k; b /= P.tiles_k;
+    const int tap = b % (P.R * P.S);
+    const int split = b / (P.R * P.S);
+    const int r = tap / P.S, s = tap % P.S;
+    const int k0 = tk * BM, c0 = tc * BN;
+    const int oh = r * P.dh - P.ph, ow = s * P.dw - P.pw;
+
+    const int bp_per_64 = 64 / BP;                           // steps_per_split counts 64-pixel units
+    const int step0 = split * P.steps_per_split * bp_per_64;
+    const int total_steps = (P.P + BP - 1) / BP;
+    int nsteps = total_steps - step0;
+    if (nsteps > P.steps_per_split * bp_per_64) nsteps = P.steps_per_split * bp_per_64;
+    if (nsteps < 0) nsteps = 0;
+
+    // ---- fixed per-thread parts of the offsets ----------------------------------------------
+    unsigned g_off[PG], x_add[PX];
+    int x_row[PX];
+#pragma unroll
+    for (int i = 0; i < PG; ++i) {
+        int row = i * RPG + tid / CRG, pc = tid % CRG;
+        int lc = ((((pc >> 2) ^ (row & GMG)) << 2) | (pc & 3));
+        int k = k0 + lc * 8;
+        g_off[i] = (k < P.K) ? (unsigned)((row * P.K + k) * 2) : kOutOfRange;
+    }
+#pragma unroll
+    for (int i = 0; i < PX; ++i) {
+        int row = i * RPX + tid / CRX, pc = tid % CRX;
+        int lc = ((((pc >> 2) ^ (row & GMX)) << 2) | (pc & 3));
+        int c = c0 + lc * 8;
+        x_row[i] = row;
+        if (LINEAR) x_add[i] = (c < P.C) ? (unsigned)((row * P.C + c) * 2) : kOutOfRange;
+        else x_add[i] = (c < P.C) ? (unsigned)(c * 2) : kOutOfRange;
+    }
+    const int4v rsrcX = make_rsrc(P.X, (unsigned)(P.N * P.H * P.W * P.C) * 2u);
+
+    // x offset table of one step: lane t < BP decodes pixel p0 + t
+    auto fill_table = [&](int step, int slot) {
+        if (LINEAR) return;
+        if (tid < BP) {
+            int p = (step0 + step) * BP + tid;
+            unsigned off = kOutOfRange;
+            if (p < P.P) {
+                int n = p / (P.Ho * P.Wo);
+                int rem = p - n * (P.Ho * P.Wo);
+                int ho = rem / P.Wo, wo = rem - ho * P.Wo;
+                int h = ho * P.sh + oh, w = wo * P.sw + ow;
+                if ((unsigned)h < (unsigned)P.H && (unsigned)w < (unsigned)P.W)
+                    off = (unsigned)((((n * P.H + h) * P.W + w) * P.C) * 2);
+            }
+            xtab[slot * BP + tid] = off;
+        }
+    };
+
+    auto issue = [&](int step, int stage) {
+        const int p0 = __builtin_amdgcn_readfirstlane((step0 + step) * BP);
+        const unsigned sbase = lds0 + stage * STAGE + wave * 1024;
+        // dy: descriptor starts at pixel p0 and ends with the tensor
+        const int4v rsrcG = make_rsrc(P.G + (long)p0 * P.K, (unsigned)((P.P - p0) * P.K) * 2u);
+#pragma unroll
+        for (int i = 0; i < PG; ++i) dma16(g_off[i], rsrcG, 0, sbase + i * RPG * BM * 2);
+        if (LINEAR) {
+            const int4v rsrcL = make_rsrc(P.X + (long)p0 * P.C, (unsigned)((P.P - p0) * P.C) * 2u);
+#pragma unroll
+            for (int i = 0; i < PX; ++i) dma16(x_add[i], rsrcL, 0, sbase + GBYTES + i * RPX * BN * 2);
+        } else {
+#pragma unroll
+            for (int i = 0; i < PX; ++i) {
+                unsigned xo = xtab[stage * BP + x_row[i]];
+                unsigned voff = ((xo | x_add[i]) & kOutOfRange) ? kOutOfRange : xo + x_add[i];
+                dma16(voff, rsrcX, 0, sbase + GBYTES + i * RPX * BN * 2);
+            }
+        }
+    };
+
+    float16v acc[FM][FN];
+#pragma unroll
+    for (int a = 0; a < FM; ++a)
+#pragma unroll
+        for (int c = 0; c < FN; ++c)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) acc[a][c][e] = 0.f;
+
+    const int grp = lane >> 4, gl = lane & 15;
+    const int frag_row = 8 * (grp >> 1) + (gl >> 2);
+    const int frag_col = 16 * (grp & 1) + 4 * (gl & 3);
+
+    auto compute = [&](int stage) {
+        const unsigned char* sg = smem + stage * STAGE;
+        const unsigned char* sx = sg + GBYTES;
+#pragma unroll
+        for (int kk = 0; kk < BP / 16; ++kk) {
+            half8 fa[FM], fb[FN];
+            const int row = kk * 16 + frag_row;
+#pragma unroll
+            for (int a = 0; a < FM; ++a) {
+                int col = wm * WM + a * 32 + frag_col;
+                half4 lo = lds_read_tr16(sg + sw_off<BM>(row, col));
+                half4 hi = lds_read_tr16(sg + sw_off<BM>(row + 4, col));
+                fa[a] = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+            }
+#pragma unroll
+            for (int c = 0; c < FN; ++c) {
+                int col = wn * WN + c * 32 + frag_col;
+                half4 lo = lds_read_tr16(sx + sw_off<BN>(row, col));
+                half4 hi = lds_read_tr16(sx + sw_off<BN>(row + 4, col));
+                fb[c] = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+            }
+#pragma unroll
+            for (int a = 0; a < FM; ++a)
+#pragma unroll
+                for (int c = 0; c < FN; ++c)
+                    acc[a][c] = __builtin_amdgcn_mfma_f32_32x32x16_f16(fa[a], fb[c], acc[a][c], 0, 0, 0);
+        }
+    };
+
+    // ---- ring pipeline ---------------------------------------------------------------------------
+    if (nsteps > 0) {
+#pragma unroll
+        for (int q = 0; q < S; ++q)
+            if (q < nsteps) fill_table(q, q);
+        if (!LINEAR) __syncthreads();
+        int issued = 0;
+#pragma unroll
+        for (int q = 0; q < S - 1; ++q)
+            if (q < nsteps) { issue(q, q); ++issued; }
+        int cs = 0, is = (S - 1) % S;
+        for (int it = 0; it < nsteps; ++it) {
+            if (it + S - 2 < nsteps) wait_vmcnt<INFLIGHT>(); else wait_vmcnt<0>();
+            if (!LINEAR) asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");   // table writes landed
+            __builtin_amdgcn_s_barrier();
+            if (issued < nsteps) {
+                issue(issued, is);
+                ++issued;
+                is = (is + 1 == S) ? 0 : is + 1;
+            }
+            // table of step it+S (read by the issue of the next iteration) reuses the slot of
+            // step `it`, whose loads were issued S-1 iterations ago
+            if (it + S < nsteps) fill_table(it + S, cs);
+            compute(cs);
+            cs = (cs + 1 == S) ? 0 : cs + 1;
+        }
+    }
+
+    // ---- store the fp32 tile: lanes 0..31 hold consecutive channels of one filter row ------
+    const long numel = (long)P.K * P.R * P.S * P.C;
+    float* out = P.out + (long)split * numel;
+    const int l32 = lane & 31, lhi = lane >> 5;
+#pragma unroll
+    for (int a = 0; a < FM; ++a)
+#pragma unroll
+        for (int c = 0; c < FN; ++c) {
+            int col = c0 + wn * WN + c * 32 + l32;
+            if (col >= P.C) continue;
+#pragma unroll
+            for (int e = 0; e < 16; ++e) {
+                int k = k0 + wm * WM + a * 32 + 8 * (e >> 2) + 4 * lhi + (e & 3);
+                if (k < P.K) out[((long)k * P.R * P.S + tap) * P.C + col] = acc[a][c][e];
+            }
+        }
+}
+
+template <int BM, int BN, int WGM, int WGN, int S, int BP>
+static hipError_t launch_wdma(const WgradParams& P, hipStream_t st)
+{
+    constexpr size_t lds = (size_t)S * BP * (BM + BN) * 2 + (size_t)S * BP * sizeof(unsigned);
+    static_assert(lds <= 160 * 1024, "LDS budget");
+    const bool linear = P.R == 1 && P.S == 1 && P.sh == 1 && P.sw == 1 && P.ph == 0 && P.pw == 0;
+    static bool configured = false;
+    if (!configured) {
+        hipError_t e = hipFuncSetAttribute(
+            reinterpret_cast<const void*>(&wgrad_dma_kernel<BM, BN, WGM, WGN, S, BP, false>),
+            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        if (e != hipSuccess) return e;
+        e = hipFuncSetAttribute(
+            reinterpret_cast<const void*>(&wgrad_dma_kernel<BM, BN, WGM, WGN, S, BP, true>),
+            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        if (e != hipSuccess) return e;
+        configured = true;
+    }
+    long blocks = (long)P.tiles_c * P.tiles_k * P.R * P.S * P.splits;
+    if (linear)
+        hipLaunchKernelGGL((wgrad_dma_kernel<BM, BN, WGM, WGN, S, BP, true>), dim3((unsigned)blocks),
+                           dim3(64 * WGM * WGN), lds, st, P);
+    else
+        hipLaunchKernelGGL((wgrad_dma_kernel<BM, BN, WGM, WGN, S, BP, false>), dim3((unsigned)blocks),
+                           dim3(64 * WGM * WGN), lds, st, P);
+    return hipGetLastError();
+}
+
+const WgradVariant kWgradDmaVariants[kNumWgradDmaVariants] = {
+    {128, 128, "wgrad_dma_128x128x64_4w_s2"},
+    {128, 128, "wgrad_dma_128x128x32_4w_s3"},
+    {256, 256, "wgrad_dma_256x256x64_8w_s2"},
+    {256, 256, "wgrad_dma_256x256x32_8w_s3"},
+    {64, 128, "wgrad_dma_64x128x64_4w_s3"},
+    {256, 128, "wgrad_dma_256x128x32_8w_s3"},
+    {64, 256, "wgrad_dma_64x256x64_4w_s2"},
+    {64, 64, "wgrad_dma_64x64x64_4w_s3"},
+    {128, 64, "wgrad_dma_128x64x64_4w_s3"},
+};
+
+hipError_t launch_wgrad_dma(int variant, const WgradParams& P, hipStream_t st)
+{
+    switch (variant) {
+        case 0: return launch_wdma<128, 128, 2, 2, 2, 64>(P, st);
+        case 1: return launch_wdma<128, 128, 2, 2, 3, 32>(P, st);
+        case 2: return launch_wdma<256, 256, 2, 4, 2, 64>(P, st);
+        case 3: return launch_wdma<256, 256, 2, 4, 3, 32>(P, st);
+        case 4: return launch_wdma<64, 128, 1, 4, 3, 64>(P, st);
+        case 5: return launch_wdma<256, 128, 4, 2, 3, 32>(P, st);
+        case 6: return launch_wdma<64, 256, 1, 4, 2, 64>(P, st);
+        case 7: return launch_wdma<64, 64, 2, 2, 3, 64>(P, st);
+        case 8: return launch_wdma<128, 64, 2, 2, 3, 64>(P, st);
+        default: return hipErrorInvalidValue;
+    }
+}
+
+}  // namespace sdconv
