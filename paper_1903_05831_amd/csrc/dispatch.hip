@@ -114,6 +114,8 @@ Plan plan_fwd(const Geom& g)
 
 Plan plan_dgrad(const Geom& g)
 {
+    if (!force_direct() && g.C <= 4 && thin_dgrad_mfma_supported(g) && !env_int("SDCONV_NO_THIN_MFMA_DGRAD", 0))
+        return Plan{ROUTE_THIN, 1, 1, align256(thin_dgrad_mfma_workspace_bytes(g)), "thin_dgrad_mfma"};
     if (!force_direct() && g.C <= 4 && g.K % 8 == 0 && g.sh * g.sw <= kMaxClasses &&
         thin_dgrad_lds_bytes(g) <= 64 * 1024)
         return Plan{ROUTE_THIN, 0, 1, align256((size_t)g.K * g.R * g.S * g.C * sizeof(__half)), "thin_dgrad"};
@@ -199,6 +201,7 @@ hipError_t run_fwd(const Geom& g, const Plan& p, const __half* x, const __half* 
 hipError_t run_dgrad(const Geom& g, const Plan& p, const __half* dy, const __half* w, __half* dx, void* ws, hipStream_t st)
 {
     if (p.route == ROUTE_DIRECT) return launch_direct_dgrad(g, dy, w, dx, st);
+    if (p.route == ROUTE_THIN && p.variant == 1) return launch_thin_dgrad_mfma(g, dy, w, dx, ws, st);
     __half* wT = static_cast<__half*>(ws);
     hipError_t e = launch_filter_transpose(w, wT, g.K, g.R * g.S, g.C, st);
     if (e != hipSuccess) return e;

@@ -26,6 +26,21 @@ struct ThinDgradParams {
     int class_block_start[17];
 };
 
+struct ThinDgradMfmaParams {
+    const __half* G;     // upstream gradient [N][Ho][Wo][K]
+    const __half* Wm;    // merged filter [RP*SP][K/8][16 slots][8]
+    __half* DX;          // [N][H][W][C]
+    int N, H, W, C, K, R, S;
+    int sh, sw, ph, pw, dh, dw, Ho, Wo;
+    int ohmin, owmin, RP, SP;   // window of dy displacements over all parity classes
+    int tiles_i, tiles_j;       // 8x32 macro-pixel tiles
+};
+
+bool thin_dgrad_mfma_supported(const Geom& g);
+size_t thin_dgrad_mfma_workspace_bytes(const Geom& g);
+hipError_t launch_thin_dgrad_mfma(const Geom& g, const __half* dy, const __half* w, __half* dx, void* ws,
+                                  hipStream_t st);
+
 bool thin_supported(const Geom& g);
 size_t thin_dgrad_lds_bytes(const Geom& g);
 hipError_t launch_thin_dgrad(const Geom& g, const __half* dy, const __half* wT, __half* dx, hipStream_t st);

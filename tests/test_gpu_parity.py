@@ -48,6 +48,10 @@ SMALL = [
     (1, 33, 70, 1, 8, 5, 8, (2, 1), (2, 3), (1, 1)),     # thin-input route, one channel, S = 8
     (1, 20, 50, 2, 16, 7, 7, (3, 2), (3, 3), (1, 1)),    # thin-input route, stride 3x2
     (1, 70, 9, 3, 64, 8, 1, (1, 1), (0, 0), (1, 1)),     # thin-input route, R = 8, S = 1
+    (2, 37, 45, 3, 64, 3, 3, (1, 1), (1, 1), (1, 1)),    # thin dgrad on MFMA, stride 1
+    (1, 41, 70, 4, 32, 5, 5, (2, 2), (2, 2), (1, 1)),    # thin dgrad on MFMA, K = 32, C = 4
+    (1, 35, 67, 2, 64, 3, 4, (2, 1), (1, 2), (1, 1)),    # thin dgrad on MFMA, stride 2x1, C = 2
+    (1, 30, 50, 3, 64, 3, 3, (2, 2), (2, 2), (2, 2)),    # thin dgrad on MFMA, dilation 2
     (1, 3, 3, 8, 8, 3, 3, (1, 1), (0, 0), (1, 1)),       # single output pixel
     (1, 1, 1, 8, 8, 1, 1, (1, 1), (0, 0), (1, 1)),       # everything is 1
     (1, 6, 6, 64, 64, 3, 3, (1, 1), (3, 3), (1, 1)),     # pad larger than needed
