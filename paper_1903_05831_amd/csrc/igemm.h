@@ -32,6 +32,9 @@ extern const IgemmVariant kIgemmVariants[kNumIgemmVariants];
 constexpr int kNumIgemmDmaVariants = 12;
 extern const IgemmVariant kIgemmDmaVariants[kNumIgemmDmaVariants];
 hipError_t launch_igemm_dma(int variant, const IgemmParams& P, hipStream_t st);
+constexpr int kNumIgemmPersVariants = 10;
+extern const IgemmVariant kIgemmPersVariants[kNumIgemmPersVariants];
+hipError_t launch_igemm_pers(int variant, const IgemmParams& P, hipStream_t st);
 hipError_t launch_igemm(int variant, const IgemmParams& P, int total_tiles, hipStream_t st);
 hipError_t launch_filter_transpose(const __half* w, __half* wT, int K, int RS, int C, hipStream_t st);
 
