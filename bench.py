@@ -36,6 +36,11 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--detail", type=str, default="", help="write per-layer timings (JSON) to this file")
+    ap.add_argument("--calib-copy-mib", type=int, default=0,
+                    help="run one plain streaming kernel over this many MiB first (a known-size reference "
+                         "dispatch for scaling FETCH_SIZE / WRITE_SIZE counters)")
+    ap.add_argument("--traffic-file", type=str, default=os.path.join(ROOT, "profiles", "dominant_kernel_traffic.json"),
+                    help="measured HBM traffic per launch of the dominant kernel (from the pmc runs)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on exactly one GPU (no collectives are part of it); use --gpus 1",
@@ -54,6 +59,13 @@ def main() -> int:
     torch.cuda.set_device(dev)
     stream = torch.cuda.current_stream().cuda_stream
     layers = workloads.CONFIGS[CONFIG_ID]
+
+    if args.calib_copy_mib > 0:
+        src = torch.ones(args.calib_copy_mib << 18, dtype=torch.float32, device=dev)   # MiB / 4 B
+        dst = torch.empty_like(src)
+        torch.neg(src, out=dst)      # an elementwise kernel: reads N MiB, writes N MiB (copy_ would use a DMA engine)
+        torch.cuda.synchronize()
+        del src, dst
 
     # ---- device-resident synthetic inputs --------------------------------------------------
     gen = torch.Generator(device=dev)
@@ -128,9 +140,10 @@ def main() -> int:
         ms = sum(ev[s][i][0].elapsed_time(ev[s][i][1]) for s in range(args.steps)) / args.steps
         per_call.append({"layer": c[0].name, "pass": c[1], "kernel": c[2], "us": ms * 1e3,
                          "tflops": c[3] / ms / 1e9, "pct_peak": 100 * c[3] / ms / 1e9 / PEAK_F16_TFLOPS})
-        gk = groups.setdefault(c[2], {"ms": 0.0, "flops": 0.0, "launches": 0, "pass": c[1]})
+        gk = groups.setdefault(c[2], {"ms": 0.0, "flops": 0.0, "launches": 0, "pass": c[1], "bytes": 0.0})
         gk["ms"] += ms
         gk["flops"] += c[3]
+        gk["bytes"] += c[0].compulsory_bytes(c[1])
         gk["launches"] += 1
     unscale_ms = sum(ev[s][-1][0].elapsed_time(ev[s][-1][1]) for s in range(args.steps)) / args.steps
     instrumented_ms = sum(g["ms"] for g in groups.values()) + unscale_ms
@@ -145,7 +158,15 @@ def main() -> int:
     roofline = {"kernel": dom_name, "bound": "mfma", "achieved": achieved, "peak": PEAK_F16_TFLOPS,
                 "unit": "TFLOP/s", "frac": achieved / PEAK_F16_TFLOPS, "traffic": None,
                 "avg_launch_us": dom_avg_ms * 1e3, "launches_per_step": dom["launches"],
-                "flop_per_launch": dom_flops}
+                "flop_per_launch": dom_flops, "algorithmic_bytes_per_launch": dom["bytes"] / dom["launches"]}
+    try:
+        with open(args.traffic_file) as f:
+            tr = json.load(f)
+        if tr.get("kernel") == dom_name:
+            roofline["traffic"] = tr.get("hbm_bytes_per_launch")
+            roofline["traffic_note"] = tr.get("note")
+    except (OSError, ValueError):
+        pass
     unscale_gbs = 8.0 * dw_total / unscale_ms / 1e6
 
     # ---- the named target layers: 3x3 convs of res3/res4 ----------------------------------------
