@@ -15,9 +15,11 @@ __device__ __forceinline__ int4v make_rsrc(const void* p, unsigned bytes)
 {
     unsigned long long a = reinterpret_cast<unsigned long long>(p);
     int4v r;
-    r.x = (int)(unsigned)a;
-    r.y = (int)((a >> 32) & 0xffffu);
-    r.z = (int)bytes;
+    // readfirstlane pins the words to scalar registers: the descriptor is an "s" operand of
+    // the load and the compiler may otherwise keep a copy in vector registers under pressure
+    r.x = __builtin_amdgcn_readfirstlane((int)(unsigned)a);
+    r.y = __builtin_amdgcn_readfirstlane((int)((a >> 32) & 0xffffu));
+    r.z = __builtin_amdgcn_readfirstlane((int)bytes);
     r.w = 0x00020000;
     return r;
 }

@@ -35,6 +35,9 @@ hipError_t launch_igemm_dma(int variant, const IgemmParams& P, hipStream_t st);
 constexpr int kNumIgemmPersVariants = 10;
 extern const IgemmVariant kIgemmPersVariants[kNumIgemmPersVariants];
 hipError_t launch_igemm_pers(int variant, const IgemmParams& P, hipStream_t st);
+constexpr int kNumIgemmWsVariants = 10;
+extern const IgemmVariant kIgemmWsVariants[kNumIgemmWsVariants];
+hipError_t launch_igemm_ws(int variant, const IgemmParams& P, hipStream_t st);
 hipError_t launch_igemm(int variant, const IgemmParams& P, int total_tiles, hipStream_t st);
 hipError_t launch_filter_transpose(const __half* w, __half* wT, int K, int RS, int C, hipStream_t st);
 

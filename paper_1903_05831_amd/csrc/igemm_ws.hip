@@ -1,0 +1,351 @@
+// Implicit-GEMM forward / data-gradient kernel with separate fetching and multiplying waves.
+//
+// Same tiles, LDS layout, swizzle and contraction order as igemm_dma.hip.  What differs is who
+// sends the global->LDS loads.  A wave that issues buffer_load ... lds stalls until the texture
+// path has taken the instruction (about 16-20 cycles per 1 KiB instruction, per CU), and while
+// it stalls it cannot feed the matrix pipe.  When every wave fetches and then multiplies, all
+// waves of a SIMD stall together and the fetch time adds to the MFMA time.  Here
+//   NP > 0 : NP extra waves do nothing but fetch (they own no part of the tile), the WGM x WGN
+//            multiplying waves never touch global memory until the epilogue;
+//   NP == 0: the upper half of the multiplying waves fetches for everybody.  With two waves per
+//            SIMD (wave w and w + NWC/2 share one) the lower wave multiplies while the upper one
+//            is stalled in its burst of loads, then the upper one multiplies.
+// One workgroup barrier per contraction step, shared by both kinds of wave, orders the ring.
+//
+// Row addressing is computed once per workgroup by all threads (one tile row each: byte offset
+// of the pixel at tap displacement 0 and a bit mask of the taps inside the image) and handed to
+// the fetching waves through LDS.
+#include "common.h"
+#include "igemm.h"
+#include "dma.h"
+
+namespace sdconv {
+
+typedef _Float16 half8 __attribute__((ext_vector_type(8)));
+typedef _Float16 half4 __attribute__((ext_vector_type(4)));
+typedef float float16v __attribute__((ext_vector_type(16)));
+
+template <int MODE, int BM, int BN, int WGM, int WGN, int S, int BK, int NP>
+__global__ __launch_bounds__(64 * (WGM * WGN + NP)) void igemm_ws_kernel(IgemmParams P)
+{
+    constexpr int NWC = WGM * WGN;                  // multiplying waves
+    constexpr int NW = NWC + NP, NT = 64 * NW;
+    constexpr int NI = NP ? NP : NWC / 2;           // fetching waves
+    constexpr int IW0 = NP ? NWC : NWC / 2;         // first fetching wave
+    constexpr int WM = BM / WGM, WN = BN / WGN;
+    constexpr int FM = WM / 32, FN = WN / 32;
+    constexpr int CPR = BK / 8;                     // 16-byte chunks per tile row
+    constexpr int ROWB = BK * 2;                    // bytes per tile row
+    constexpr int SWS = (CPR == 8) ? 1 : 2;         // swizzle: chunk ^= (row >> SWS) & (CPR-1)
+    constexpr int RPP = 64 * NI / CPR;              // tile rows one pass of the fetching waves covers
+    constexpr int PA = BM / RPP, PB = BN / RPP;     // loads per fetching thread and stage
+    constexpr int STAGE = (BM + BN) * ROWB;         // bytes
+    constexpr int INFLIGHT = (S - 2) * (PA + PB);   // loads a fetching wave may leave outstanding
+    static_assert(WM % 32 == 0 && WN % 32 == 0 && BM % RPP == 0 && BN % RPP == 0, "tile shape");
+    static_assert(S >= 2 && INFLIGHT < 64, "pipeline depth");
+    static_assert(BK == 64 || BK == 32, "contraction step");
+    static_assert(NI >= 1 && (NP > 0 || NWC % 2 == 0), "fetching waves");
+
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+    const unsigned lds0 = (unsigned)(size_t)(__attribute__((address_space(3))) unsigned char*)smem;
+    int* tap_oh = reinterpret_cast<int*>(smem + S * STAGE);
+    int* tap_ow = tap_oh + kMaxTaps;
+    int* tap_bo = tap_ow + kMaxTaps;      // byte offset of the tap inside a filter row
+    int* tap_ad = tap_bo + kMaxTaps;      // byte displacement of the tap in the source image
+    int* tap_cnt = tap_ad + kMaxTaps;     // [4]
+    unsigned* row_off = reinterpret_cast<unsigned*>(tap_cnt + 4);                    // [BM]
+    unsigned long long* row_mask = reinterpret_cast<unsigned long long*>(row_off + BM);   // [BM]
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+
+    // ---- which tile (runs of 8 consecutive tiles per XCD, runs interleaved over the XCDs) ----
+    constexpr int kRun = 8;
+    const int xcd = blockIdx.x & 7, idx = blockIdx.x >> 3;
+    const int tile = ((idx / kRun) * 8 + xcd) * kRun + (idx % kRun);
+    if (tile >= P.total_tiles) return;
+    const int tn = tile % P.tiles_n;
+    int tm = tile / P.tiles_n;
+    int cls = 0;
+    while (cls + 1 < P.nclasses && tm >= P.class_tile_start[cls + 1]) ++cls;
+    tm -= P.class_tile_start[cls];
+    const int ca = cls / P.sw_cls, cb = cls % P.sw_cls;
+
+    int Hi, Wj, mh, mw, eh, ew;
+    if (MODE == 0) { Hi = P.Hd; Wj = P.Wd; mh = P.sh; mw = P.sw; eh = 1; ew = 1; }
+    else {
+        Hi = (P.Hd - ca + P.sh - 1) / P.sh; Wj = (P.Wd - cb + P.sw - 1) / P.sw;
+        mh = 1; mw = 1; eh = P.sh; ew = P.sw;
+    }
+    const int Mcls = P.NB * Hi * Wj;
+    const int m0 = tm * BM, n0 = tn * BN;
+
+    // ---- tap table -------------------------------------------------------------------
+    if (wave == 0) {
+        const int ntap_all = P.R * P.S;
+        bool ok = false;
+        int oh = 0, ow = 0;
+        const int r = lane / P.S, s = lane % P.S;
+        if (lane < ntap_all) {
+            if (MODE == 0) { ok = true; oh = r * P.dh - P.ph; ow = s * P.dw - P.pw; }
+            else {
+                int th = ca + P.ph - r * P.dh, tw = cb + P.pw - s * P.dw;
+                ok = (th % P.sh == 0) && (tw % P.sw == 0);
+                oh = th / P.sh; ow = tw / P.sw;
+            }
+        }
+        unsigned long long mask = __ballot(ok);
+        int pos = __popcll(mask & ((1ull << lane) - 1ull));
+        if (ok) {
+            tap_oh[pos] = oh; tap_ow[pos] = ow;
+            tap_bo[pos] = (r * P.S + s) * P.Cs * 2;
+            tap_ad[pos] = (oh * P.Ws + ow) * P.Cs * 2;
+        }
+        if (lane == 0) tap_cnt[0] = __popcll(mask);
+    }
+    __syncthreads();
+    const int ntaps = __builtin_amdgcn_readfirstlane(tap_cnt[0]);
+    const int kchunks = (P.Cs + BK - 1) / BK;
+    const int nk = ntaps * kchunks;
+
+    // ---- row table: one tile row per thread ------------------------------------------------
+    for (int r = tid; r < BM; r += NT) {
+        int m = m0 + r;
+        unsigned off = 0;
+        unsigned long long mk = 0ull;
+        if (m < Mcls) {
+            int n = m / (Hi * Wj);
+            int rem = m - n * (Hi * Wj);
+            int i = rem / Wj, j = rem - i * Wj;
+            int ih = i * mh, jw = j * mw;
+            off = (unsigned)((((n * P.Hs + ih) * P.Ws + jw) * P.Cs) * 2);
+            for (int t = 0; t < ntaps; ++t) {
+                int hs = ih + tap_oh[t], ws = jw + tap_ow[t];
+                if ((unsigned)hs < (unsigned)P.Hs && (unsigned)ws < (unsigned)P.Ws) mk |= 1ull << t;
+            }
+        }
+        row_off[r] = off;
+        row_mask[r] = mk;
+    }
+    __syncthreads();
+
+    const bool fetcher = wave >= IW0;
+
+    // ---- fetching side ---------------------------------------------------------------------
+    const int ft = tid - IW0 * 64;                  // thread index among the fetching threads
+    const int fw = wave - IW0;                      // fetching wave index
+    const int lrow = ft / CPR;                      // 0 .. RPP-1 (fetching threads only)
+    const int kc = ft % CPR;                        // 16-byte chunk slot in LDS this lane fills
+    unsigned a_off[PA];
+    unsigned long long a_mask[PA];
+    unsigned b_off[PB];
+    const bool partial = (P.Cs % BK) != 0;          // last channel chunk is short
+    if (fetcher) {
+#pragma unroll
+        for (int p = 0; p < PA; ++p) {
+            const int r = lrow + RPP * p;
+            const int kcl = kc ^ ((r >> SWS) & (CPR - 1));      // logical chunk this lane fetches
+            a_off[p] = row_off[r] + (unsigned)(kcl * 16);
+            a_mask[p] = row_mask[r];
+        }
+#pragma unroll
+        for (int p = 0; p < PB; ++p) {
+            const int r = lrow + RPP * p;
+            const int kcl = kc ^ ((r >> SWS) & (CPR - 1));
+            const int n = n0 + r;
+            b_off[p] = (n < P.Cd) ? (unsigned)((n * P.b_row_pitch + kcl * 8) * 2) : kOutOfRange;
+        }
+    }
+    const int4v rsrcA = make_rsrc(P.A, (unsigned)(P.NB * P.Hs * P.Ws * P.Cs) * 2u);
+    const int4v rsrcB = make_rsrc(P.B, (unsigned)(P.Cd * P.b_row_pitch) * 2u);
+
+    int nx_tap = 0, nx_kc = 0;          // contraction step the next issue() fetches (wave-uniform)
+    auto issue = [&](int stage) {
+        const unsigned cbytes = (unsigned)__builtin_amdgcn_readfirstlane(nx_kc * ROWB);
+        const unsigned ad = (unsigned)tap_ad[nx_tap];
+        const unsigned bo = (unsigned)__builtin_amdgcn_readfirstlane(tap_bo[nx_tap]);
+        const unsigned sbase = (unsigned)__builtin_amdgcn_readfirstlane((int)(lds0 + stage * STAGE + fw * 1024));
+        const int cleft = P.Cs - nx_kc * BK;        // channels left from this chunk's start
+#pragma unroll
+        for (int p = 0; p < PA; ++p) {
+            const int r = lrow + RPP * p;
+            const int kcl = kc ^ ((r >> SWS) & (CPR - 1));
+            unsigned ok = (unsigned)(a_mask[p] >> nx_tap) & 1u;
+            if (partial && kcl * 8 >= cleft) ok = 0;
+            unsigned voff = ok ? a_off[p] + ad : kOutOfRange;
+            dma16(voff, rsrcA, cbytes, sbase + p * RPP * ROWB);
+        }
+#pragma unroll
+        for (int p = 0; p < PB; ++p) {
+            const int r = lrow + RPP * p;
+            const int kcl = kc ^ ((r >> SWS) & (CPR - 1));
+            unsigned voff = (partial && kcl * 8 >= cleft) ? kOutOfRange : b_off[p];
+            dma16(voff, rsrcB, bo + cbytes, sbase + BM * ROWB + p * RPP * ROWB);
+        }
+        // taps vary fastest: the taps of a 3x3 re-read nearly the same pixels of one channel
+        // slab back to back, while it is still in L2
+        int t1 = nx_tap + 1;
+        bool wrap = t1 == ntaps;
+        nx_tap = __builtin_amdgcn_readfirstlane(wrap ? 0 : t1);
+        nx_kc = __builtin_amdgcn_readfirstlane(wrap ? nx_kc + 1 : nx_kc);
+    };
+
+    if (NP > 0 && fetcher) {
+        // ---- dedicated fetching wave: S-1 steps ahead of the multipliers ---------------------
+#pragma unroll
+        for (int s = 0; s < S - 1; ++s)
+            if (s < nk) issue(s);
+        int is = (S - 1) % S;
+        for (int it = 0; it < nk; ++it) {
+            if (it + S - 2 < nk) wait_vmcnt<INFLIGHT>(); else wait_vmcnt<0>();
+            __builtin_amdgcn_s_barrier();           // step it is in LDS; stage of step it-1 is free
+            if (it + S - 1 < nk) { issue(is); is = (is + 1 == S) ? 0 : is + 1; }
+        }
+        return;
+    }
+
+    // ---- multiplying side ------------------------------------------------------------------
+    const int wm = wave / WGN, wn = wave % WGN;
+    float16v acc[FN][FM];
+#pragma unroll
+    for (int a = 0; a < FN; ++a)
+#pragma unroll
+        for (int b = 0; b < FM; ++b)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) acc[a][b][e] = 0.f;
+
+    const int l32 = lane & 31, lhi = lane >> 5;
+    auto compute = [&](int stage) {
+        const unsigned char* sa = smem + stage * STAGE;
+        const unsigned char* sb = sa + BM * ROWB;
+#pragma unroll
+        for (int kk = 0; kk < BK / 16; ++kk) {
+            const int chunk = kk * 2 + lhi;
+            half8 fa[FM], fb[FN];
+#pragma unroll
+            for (int b = 0; b < FM; ++b) {
+                int row = wm * WM + b * 32 + l32;
+                fa[b] = *reinterpret_cast<const half8*>(sa + row * ROWB + ((chunk ^ ((row >> SWS) & (CPR - 1))) << 4));
+            }
+#pragma unroll
+            for (int a = 0; a < FN; ++a) {
+                int row = wn * WN + a * 32 + l32;
+                fb[a] = *reinterpret_cast<const half8*>(sb + row * ROWB + ((chunk ^ ((row >> SWS) & (CPR - 1))) << 4));
+            }
+#pragma unroll
+            for (int a = 0; a < FN; ++a)
+#pragma unroll
+                for (int b = 0; b < FM; ++b)
+                    acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_f16(fb[a], fa[b], acc[a][b], 0, 0, 0);
+        }
+    };
+
+    if (NP > 0) {
+        int cs = 0;
+        for (int it = 0; it < nk; ++it) {
+            __builtin_amdgcn_s_barrier();
+            compute(cs);
+            cs = (cs + 1 == S) ? 0 : cs + 1;
+        }
+    } else {
+        // upper half of the waves fetches for the whole group, then multiplies its own share
+        if (fetcher) {
+#pragma unroll
+            for (int s = 0; s < S - 1; ++s)
+                if (s < nk) issue(s);
+        }
+        int cs = 0, is = (S - 1) % S;
+        for (int it = 0; it < nk; ++it) {
+            if (fetcher) { if (it + S - 2 < nk) wait_vmcnt<INFLIGHT>(); else wait_vmcnt<0>(); }
+            __builtin_amdgcn_s_barrier();
+            if (fetcher && it + S - 1 < nk) issue(is);
+            is = (is + 1 == S) ? 0 : is + 1;
+            compute(cs);
+            cs = (cs + 1 == S) ? 0 : cs + 1;
+        }
+    }
+
+    // ---- epilogue: fp32 -> fp16 (nearest even), 8-byte NHWC stores ----------------------------
+#pragma unroll
+    for (int b = 0; b < FM; ++b) {
+        int m = m0 + wm * WM + b * 32 + l32;
+        if (m >= Mcls) continue;
+        int n = m / (Hi * Wj);
+        int rem = m - n * (Hi * Wj);
+        int i = rem / Wj, j = rem - i * Wj;
+        int hd = i * eh + ca, wd = j * ew + cb;
+        __half* drow = P.D + ((n * P.Hd + hd) * P.Wd + wd) * P.Cd;
+#pragma unroll
+        for (int a = 0; a < FN; ++a) {
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                int col = n0 + wn * WN + a * 32 + 8 * q + 4 * lhi;
+                if (col < P.Cd) {
+                    half4 h;
+                    h[0] = (_Float16)acc[a][b][4 * q + 0];
+                    h[1] = (_Float16)acc[a][b][4 * q + 1];
+                    h[2] = (_Float16)acc[a][b][4 * q + 2];
+                    h[3] = (_Float16)acc[a][b][4 * q + 3];
+                    *reinterpret_cast<half4*>(drow + col) = h;
+                }
+            }
+        }
+    }
+}
+
+template <int MODE, int BM, int BN, int WGM, int WGN, int S, int BK, int NP>
+static hipError_t launch_ws_variant(const IgemmParams& P, hipStream_t st)
+{
+    constexpr size_t lds = (size_t)S * (BM + BN) * BK * 2 + (4 * kMaxTaps + 4) * sizeof(int) + (size_t)BM * 12;
+    static_assert(lds <= 160 * 1024, "LDS budget");
+    static bool configured = false;
+    if (!configured) {
+        hipError_t e = hipFuncSetAttribute(
+            reinterpret_cast<const void*>(&igemm_ws_kernel<MODE, BM, BN, WGM, WGN, S, BK, NP>),
+            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        if (e != hipSuccess) return e;
+        configured = true;
+    }
+    const int grid = ((P.total_tiles + 63) / 64) * 64;   // whole runs of 8 tiles on each of 8 XCDs
+    hipLaunchKernelGGL((igemm_ws_kernel<MODE, BM, BN, WGM, WGN, S, BK, NP>), dim3(grid),
+                       dim3(64 * (WGM * WGN + NP)), lds, st, P);
+    return hipGetLastError();
+}
+
+const IgemmVariant kIgemmWsVariants[kNumIgemmWsVariants] = {
+    {128, 128, "igemm_fwd_ws_128x128x64_4w2f_s3", "igemm_dgrad_ws_128x128x64_4w2f_s3"},
+    {128, 128, "igemm_fwd_ws_128x128x64_4w2f_s4", "igemm_dgrad_ws_128x128x64_4w2f_s4"},
+    {256, 256, "igemm_fwd_ws_256x256x64_8w0f_s2", "igemm_dgrad_ws_256x256x64_8w0f_s2"},
+    {256, 128, "igemm_fwd_ws_256x128x64_8w2f_s3", "igemm_dgrad_ws_256x128x64_8w2f_s3"},
+    {128, 128, "igemm_fwd_ws_128x128x64_8w2f_s3", "igemm_dgrad_ws_128x128x64_8w2f_s3"},
+    {128, 128, "igemm_fwd_ws_128x128x64_8w0f_s3", "igemm_dgrad_ws_128x128x64_8w0f_s3"},
+    {256, 128, "igemm_fwd_ws_256x128x64_8w0f_s3", "igemm_dgrad_ws_256x128x64_8w0f_s3"},
+    {128, 64, "igemm_fwd_ws_128x64x64_4w2f_s4", "igemm_dgrad_ws_128x64x64_4w2f_s4"},
+    {128, 64, "igemm_fwd_ws_128x64x64_8w0f_s4", "igemm_dgrad_ws_128x64x64_8w0f_s4"},
+    {128, 256, "igemm_fwd_ws_128x256x64_8w0f_s3", "igemm_dgrad_ws_128x256x64_8w0f_s3"},
+};
+
+#define SDCONV_WS_CASE(idx, BM, BN, WGM, WGN, S, BK, NP)                                      \
+    case 2 * (idx): return launch_ws_variant<0, BM, BN, WGM, WGN, S, BK, NP>(P, st);          \
+    case 2 * (idx) + 1: return launch_ws_variant<1, BM, BN, WGM, WGN, S, BK, NP>(P, st);
+
+hipError_t launch_igemm_ws(int variant, const IgemmParams& P, hipStream_t st)
+{
+    const int key = variant * 2 + (P.mode ? 1 : 0);
+    switch (key) {
+        SDCONV_WS_CASE(0, 128, 128, 2, 2, 3, 64, 2)
+        SDCONV_WS_CASE(1, 128, 128, 2, 2, 4, 64, 2)
+        SDCONV_WS_CASE(2, 256, 256, 2, 4, 2, 64, 0)
+        SDCONV_WS_CASE(3, 256, 128, 4, 2, 3, 64, 2)
+        SDCONV_WS_CASE(4, 128, 128, 2, 4, 3, 64, 2)
+        SDCONV_WS_CASE(5, 128, 128, 2, 4, 3, 64, 0)
+        SDCONV_WS_CASE(6, 256, 128, 4, 2, 3, 64, 0)
+        SDCONV_WS_CASE(7, 128, 64, 2, 2, 4, 64, 2)
+        SDCONV_WS_CASE(8, 128, 64, 4, 2, 4, 64, 0)
+        SDCONV_WS_CASE(9, 128, 256, 2, 4, 3, 64, 0)
+        default: return hipErrorInvalidValue;
+    }
+}
+
+}  // namespace sdconv

@@ -17,7 +17,7 @@ import torch
 import paper_1903_05831_amd as sd
 from paper_1903_05831_amd import workloads
 
-FWD_DGRAD_VARIANTS = [100, 101, 105, 106, 107, 108, 200, 201, 203, 204, 205, 206, 209]
+FWD_DGRAD_VARIANTS = [100, 101, 105, 106, 107, 108, 200, 201, 203, 206, 300, 302, 303, 306, 309]
 WGRAD_VARIANTS = [100, 101, 102, 104, 105, 107, 108]
 WGRAD_SPLITS = [1, 2, 3, 4, 6, 8, 12, 16, 24, 32, 48, 64, 96, 128, 192, 256]
 HERE = os.path.dirname(os.path.abspath(__file__))
