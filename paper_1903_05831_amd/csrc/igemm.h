@@ -35,7 +35,7 @@ hipError_t launch_igemm_dma(int variant, const IgemmParams& P, hipStream_t st);
 constexpr int kNumIgemmPersVariants = 10;
 extern const IgemmVariant kIgemmPersVariants[kNumIgemmPersVariants];
 hipError_t launch_igemm_pers(int variant, const IgemmParams& P, hipStream_t st);
-constexpr int kNumIgemmWsVariants = 10;
+constexpr int kNumIgemmWsVariants = 12;
 extern const IgemmVariant kIgemmWsVariants[kNumIgemmWsVariants];
 hipError_t launch_igemm_ws(int variant, const IgemmParams& P, hipStream_t st);
 hipError_t launch_igemm(int variant, const IgemmParams& P, int total_tiles, hipStream_t st);

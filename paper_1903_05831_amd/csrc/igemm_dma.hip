@@ -23,6 +23,7 @@
 #include "common.h"
 #include "igemm.h"
 #include "dma.h"
+#include "igemm_epilogue.h"
 
 namespace sdconv {
 
@@ -222,32 +223,11 @@ __global__ __launch_bounds__(64 * WGM * WGN) void igemm_dma_kernel(IgemmParams P
         }
     }
 
-    // ---- epilogue: fp32 -> fp16 (nearest even), 8-byte NHWC stores ----------------------------
-#pragma unroll
-    for (int b = 0; b < FM; ++b) {
-        int m = m0 + wm * WM + b * 32 + l32;
-        if (m >= Mcls) continue;
-        int n = m / (Hi * Wj);
-        int rem = m - n * (Hi * Wj);
-        int i = rem / Wj, j = rem - i * Wj;
-        int hd = i * eh + ca, wd = j * ew + cb;
-        __half* drow = P.D + ((n * P.Hd + hd) * P.Wd + wd) * P.Cd;
-#pragma unroll
-        for (int a = 0; a < FN; ++a) {
-#pragma unroll
-            for (int q = 0; q < 4; ++q) {
-                int col = n0 + wn * WN + a * 32 + 8 * q + 4 * lhi;
-                if (col < P.Cd) {
-                    half4 h;
-                    h[0] = (_Float16)acc[a][b][4 * q + 0];
-                    h[1] = (_Float16)acc[a][b][4 * q + 1];
-                    h[2] = (_Float16)acc[a][b][4 * q + 2];
-                    h[3] = (_Float16)acc[a][b][4 * q + 3];
-                    *reinterpret_cast<half4*>(drow + col) = h;
-                }
-            }
-        }
-    }
+    // ---- epilogue: through a per-wave LDS strip into 16-byte NHWC stores --------------------
+    static_assert(NW * epilogue_strip_bytes<WN>() <= S * STAGE, "epilogue strips fit in the ring");
+    __builtin_amdgcn_s_barrier();                   // everybody is done reading the last stage
+    store_tile_via_lds<FM, FN>(acc, smem + wave * epilogue_strip_bytes<WN>(), lane, m0 + wm * WM, n0 + wn * WN,
+                               Mcls, P, Hi, Wj, eh, ew, ca, cb);
 }
 
 template <int MODE, int BM, int BN, int WGM, int WGN, int S, int BK>

@@ -1,0 +1,73 @@
+// Epilogue shared by the LDS-DMA implicit-GEMM kernels: fp32 accumulators -> fp16 (nearest
+// even) -> NHWC destination, transposed through LDS so that the global stores are 16 bytes per
+// lane on consecutive chunks of a pixel row.
+//
+// A lane's accumulators of one 32x32 MFMA block (computed as B x A, i.e. transposed) are 16
+// columns of ONE pixel row, in four groups of four: stored directly they become 8-byte pieces
+// scattered over 32 rows, sixteen partial writes per 128-byte line.  Here each wave parks
+// 32 rows x WN columns in a private LDS strip (row pitch padded by 16 bytes against bank
+// conflicts) and reads it back with consecutive lanes on consecutive 16-byte chunks of a row,
+// so every store instruction writes whole 64/128-byte row segments.
+#pragma once
+#include "common.h"
+#include "igemm.h"
+
+namespace sdconv {
+
+template <int WN> constexpr int epilogue_strip_bytes() { return 32 * (WN * 2 + 16); }
+
+// acc[a][b]: block (rows b*32.., columns a*32..) of the wave's WM x WN sub-tile.
+// strip: this wave's private LDS area of epilogue_strip_bytes<WN>() bytes; the caller has made
+// sure (workgroup barrier) that nobody still reads what the strip overwrites.
+// m_base/col_base: first GEMM row / destination channel of the wave's sub-tile.
+template <int FM, int FN, typename Acc>
+__device__ __forceinline__ void store_tile_via_lds(Acc (&acc)[FN][FM], unsigned char* strip, int lane,
+                                                   int m_base, int col_base, int Mcls, const IgemmParams& P,
+                                                   int Hi, int Wj, int eh, int ew, int ca, int cb)
+{
+    typedef _Float16 h4 __attribute__((ext_vector_type(4)));
+    typedef _Float16 h8 __attribute__((ext_vector_type(8)));
+    constexpr int WN = FN * 32;
+    constexpr int CW = WN / 8;                      // 16-byte chunks per strip row
+    constexpr int RPI = 64 / CW;                    // strip rows one store instruction covers
+    constexpr int PITCH = WN * 2 + 16;
+    const int l32 = lane & 31, lhi = lane >> 5;
+    const int srow = lane / CW, schunk = lane % CW;
+    const bool linear = (eh == 1 && ew == 1);       // destination pixel index == GEMM row index
+#pragma unroll
+    for (int b = 0; b < FM; ++b) {
+#pragma unroll
+        for (int a = 0; a < FN; ++a) {
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                h4 h;
+                h[0] = (_Float16)acc[a][b][4 * q + 0];
+                h[1] = (_Float16)acc[a][b][4 * q + 1];
+                h[2] = (_Float16)acc[a][b][4 * q + 2];
+                h[3] = (_Float16)acc[a][b][4 * q + 3];
+                *reinterpret_cast<h4*>(strip + l32 * PITCH + (a * 32 + 8 * q + 4 * lhi) * 2) = h;
+            }
+        }
+        // the strip is private to the wave, and LDS operations of one wave complete in order
+#pragma unroll
+        for (int j = 0; j < 32 / RPI; ++j) {
+            const int r = j * RPI + srow;
+            h8 v = *reinterpret_cast<const h8*>(strip + r * PITCH + schunk * 16);
+            const int m = m_base + b * 32 + r;
+            const int col = col_base + schunk * 8;
+            if (m < Mcls && col < P.Cd) {
+                long pix;
+                if (linear) pix = m;
+                else {
+                    int n = m / (Hi * Wj);
+                    int rem = m - n * (Hi * Wj);
+                    int i = rem / Wj, jj = rem - i * Wj;
+                    pix = ((long)n * P.Hd + (i * eh + ca)) * P.Wd + (jj * ew + cb);
+                }
+                *reinterpret_cast<h8*>(P.D + pix * P.Cd + col) = v;
+            }
+        }
+    }
+}
+
+}  // namespace sdconv

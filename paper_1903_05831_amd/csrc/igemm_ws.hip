@@ -18,6 +18,7 @@
 #include "common.h"
 #include "igemm.h"
 #include "dma.h"
+#include "igemm_epilogue.h"
 
 namespace sdconv {
 
@@ -266,32 +267,11 @@ __global__ __launch_bounds__(64 * (WGM * WGN + NP)) void igemm_ws_kernel(IgemmPa
         }
     }
 
-    // ---- epilogue: fp32 -> fp16 (nearest even), 8-byte NHWC stores ----------------------------
-#pragma unroll
-    for (int b = 0; b < FM; ++b) {
-        int m = m0 + wm * WM + b * 32 + l32;
-        if (m >= Mcls) continue;
-        int n = m / (Hi * Wj);
-        int rem = m - n * (Hi * Wj);
-        int i = rem / Wj, j = rem - i * Wj;
-        int hd = i * eh + ca, wd = j * ew + cb;
-        __half* drow = P.D + ((n * P.Hd + hd) * P.Wd + wd) * P.Cd;
-#pragma unroll
-        for (int a = 0; a < FN; ++a) {
-#pragma unroll
-            for (int q = 0; q < 4; ++q) {
-                int col = n0 + wn * WN + a * 32 + 8 * q + 4 * lhi;
-                if (col < P.Cd) {
-                    half4 h;
-                    h[0] = (_Float16)acc[a][b][4 * q + 0];
-                    h[1] = (_Float16)acc[a][b][4 * q + 1];
-                    h[2] = (_Float16)acc[a][b][4 * q + 2];
-                    h[3] = (_Float16)acc[a][b][4 * q + 3];
-                    *reinterpret_cast<half4*>(drow + col) = h;
-                }
-            }
-        }
-    }
+    // ---- epilogue: through a per-wave LDS strip into 16-byte NHWC stores --------------------
+    static_assert(NWC * epilogue_strip_bytes<WN>() <= S * STAGE, "epilogue strips fit in the ring");
+    __builtin_amdgcn_s_barrier();                   // everybody is done reading the last stage
+    store_tile_via_lds<FM, FN>(acc, smem + wave * epilogue_strip_bytes<WN>(), lane, m0 + wm * WM, n0 + wn * WN,
+                               Mcls, P, Hi, Wj, eh, ew, ca, cb);
 }
 
 template <int MODE, int BM, int BN, int WGM, int WGN, int S, int BK, int NP>
@@ -324,6 +304,8 @@ const IgemmVariant kIgemmWsVariants[kNumIgemmWsVariants] = {
     {128, 64, "igemm_fwd_ws_128x64x64_4w2f_s4", "igemm_dgrad_ws_128x64x64_4w2f_s4"},
     {128, 64, "igemm_fwd_ws_128x64x64_8w0f_s4", "igemm_dgrad_ws_128x64x64_8w0f_s4"},
     {128, 256, "igemm_fwd_ws_128x256x64_8w0f_s3", "igemm_dgrad_ws_128x256x64_8w0f_s3"},
+    {224, 256, "igemm_fwd_ws_224x256x64_8w0f_s2", "igemm_dgrad_ws_224x256x64_8w0f_s2"},
+    {256, 256, "igemm_fwd_ws_256x256x64_8w0f_s2_1x8", "igemm_dgrad_ws_256x256x64_8w0f_s2_1x8"},
 };
 
 #define SDCONV_WS_CASE(idx, BM, BN, WGM, WGN, S, BK, NP)                                      \
@@ -344,6 +326,8 @@ hipError_t launch_igemm_ws(int variant, const IgemmParams& P, hipStream_t st)
         SDCONV_WS_CASE(7, 128, 64, 2, 2, 4, 64, 2)
         SDCONV_WS_CASE(8, 128, 64, 4, 2, 4, 64, 0)
         SDCONV_WS_CASE(9, 128, 256, 2, 4, 3, 64, 0)
+        SDCONV_WS_CASE(10, 224, 256, 1, 8, 2, 64, 0)
+        SDCONV_WS_CASE(11, 256, 256, 1, 8, 2, 64, 0)
         default: return hipErrorInvalidValue;
     }
 }
