@@ -2,14 +2,18 @@
 """Benchmark of the mixed-precision convolution hot path on one MI355X.
 
 One step = one pass of the whole path over the full ResNet-50-C4 Faster R-CNN conv
-workload (N=2 images of 800x1344 plus 512 RoIs; 53 conv layers): conv2d_fwd, conv2d_dgrad
-and conv2d_wgrad for every layer, then grad_unscale_check over all 23 454 912 fp32
-weight-gradient elements.  Inputs are synthetic (N(0,1) activations and gradients,
-He-normal weights), generated on the device before the timed region.
+workload (N=2 images of 800x1344 plus 512 RoIs; 53 conv layers), in the order of a training
+step: conv2d_fwd for every layer first to last, then last to first conv2d_dgrad and
+conv2d_wgrad of each layer, then grad_unscale_check over all 23 454 912 fp32 weight-gradient
+elements.  The two gradients of a layer depend only on the incoming gradient, not on each
+other: with --streams 2 (default) the weight gradients go to a second HIP stream (default
+priority, own workspace) and overlap the data gradients; --streams 1 keeps everything on one
+stream.  Inputs are synthetic (N(0,1) activations and gradients, He-normal weights), generated
+on the device before the timed region.
 
 Prints ONE JSON line.  `value` is algorithmic TFLOP/s of the whole step (2*N*Ho*Wo*K*R*S*C
 per pass and layer).  `roofline` is for the kernel with the largest share of the step,
-timed with HIP events on the launch stream.  `cpu_baseline` times the fp64 CPU oracle on a
+timed with HIP events on the launch stream in a second, single-stream pass over the same calls.  `cpu_baseline` times the fp64 CPU oracle on a
 bounded sample of the same workload.
 """
 from __future__ import annotations
@@ -35,6 +39,8 @@ def main() -> int:
     ap.add_argument("--steps", type=int, default=10)
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--streams", type=int, default=2, choices=(1, 2),
+                    help="2: weight gradients on a second stream, overlapping the data gradients")
     ap.add_argument("--detail", type=str, default="", help="write per-layer timings (JSON) to this file")
     ap.add_argument("--calib-copy-mib", type=int, default=0,
                     help="run one plain streaming kernel over this many MiB first (a known-size reference "
@@ -57,7 +63,10 @@ def main() -> int:
     sd.lib()   # fail loudly when the HIP library is missing
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
-    stream = torch.cuda.current_stream().cuda_stream
+    main_stream = torch.cuda.current_stream()
+    stream = main_stream.cuda_stream
+    side_stream = torch.cuda.Stream() if args.streams == 2 else None      # default priority
+    stream2 = side_stream.cuda_stream if side_stream is not None else stream
     layers = workloads.CONFIGS[CONFIG_ID]
 
     if args.calib_copy_mib > 0:
@@ -90,24 +99,35 @@ def main() -> int:
             ws_bytes = max(ws_bytes, sd.conv2d_workspace_bytes(d, pid))
         jobs.append((l, d, x, w, g, y, dx, dw))
     ws = torch.empty(ws_bytes, dtype=torch.uint8, device=dev)
+    ws2 = torch.empty(ws_bytes, dtype=torch.uint8, device=dev) if side_stream is not None else ws
     inv_scale = 1.0 / LOSS_SCALE
 
-    calls = []   # (layer, pass name, kernel name, flops, closure)
+    # (layer, pass name, kernel name, flops, closure(workspace, stream)) in training order:
+    # forward first to last, then backward last to first
+    calls = []
     for (l, d, x, w, g, y, dx, dw) in jobs:
         calls.append((l, "fwd", sd.kernel_name(d, sd.FWD), l.flops,
-                      lambda d=d, x=x, w=w, y=y: sd.conv2d_fwd(d, x, w, y, ws, stream)))
+                      lambda wsp, st, d=d, x=x, w=w, y=y: sd.conv2d_fwd(d, x, w, y, wsp, st)))
+    for (l, d, x, w, g, y, dx, dw) in reversed(jobs):
         calls.append((l, "dgrad", sd.kernel_name(d, sd.DGRAD), l.flops,
-                      lambda d=d, g=g, w=w, dx=dx: sd.conv2d_dgrad(d, g, w, dx, ws, stream)))
+                      lambda wsp, st, d=d, g=g, w=w, dx=dx: sd.conv2d_dgrad(d, g, w, dx, wsp, st)))
         calls.append((l, "wgrad", sd.kernel_name(d, sd.WGRAD), l.flops,
-                      lambda d=d, x=x, g=g, dw=dw: sd.conv2d_wgrad(d, x, g, dw, ws, stream)))
+                      lambda wsp, st, d=d, x=x, g=g, dw=dw: sd.conv2d_wgrad(d, x, g, dw, wsp, st)))
 
     def unscale():
         sd.grad_unscale_check(dw_flat, dw_total, inv_scale, flag, stream)
 
     def step():
         for c in calls:
-            c[4]()
+            if c[1] == "wgrad":
+                c[4](ws2, stream2)
+            else:
+                c[4](ws, stream)
+        if side_stream is not None:
+            main_stream.wait_stream(side_stream)      # all weight gradients done before the unscale
         unscale()
+        if side_stream is not None:
+            side_stream.wait_stream(main_stream)      # the next step's gradients follow this unscale
 
     flops_per_step = 3 * sum(l.flops for l in layers)
 
@@ -128,7 +148,7 @@ def main() -> int:
     for s in range(args.steps):
         for i, c in enumerate(calls):
             ev[s][i][0].record()
-            c[4]()
+            c[4](ws, stream)
             ev[s][i][1].record()
         ev[s][-1][0].record()
         unscale()
@@ -182,8 +202,9 @@ def main() -> int:
         "dtype": "f16", "data": "synthetic",
         "config": {"workload": "configs[4]: " + workloads.CONFIG_NAMES[CONFIG_ID],
                    "layers": len(layers), "gflop_per_step": flops_per_step / 1e9,
-                   "passes": "fwd+dgrad+wgrad per layer, then grad_unscale_check on %d fp32" % dw_total,
-                   "loss_scale": LOSS_SCALE},
+                   "passes": "fwd of all layers, then dgrad+wgrad last to first, then grad_unscale_check "
+                             "on %d fp32" % dw_total,
+                   "streams": args.streams, "loss_scale": LOSS_SCALE},
         "pct_fp16_mfma_peak": 100 * value / PEAK_F16_TFLOPS,
         "pct_peak_res3_res4_3x3": target_pct,
         "roofline": roofline,
