@@ -1,0 +1,262 @@
+// Stride-1 3x3-class forward / data-gradient kernel that keeps the input patch in LDS.
+//
+// The implicit-GEMM kernels fetch the activation tile once per filter tap: a 3x3 layer reads
+// (nearly) the same pixels nine times from L2 and the global->LDS path, not the MFMA pipe,
+// sets the pace.  Here a workgroup owns a TH x TW block of output pixels of one image and,
+// per 64-channel slab, loads the (TH+2) x (TW+2) input patch ONCE (halo included, pixels
+// outside the image zero-filled by the buffer range check = the padding).  The nine taps then
+// read their A fragments from the same patch at a per-tap pixel displacement; only the filter
+// slab (BN rows x 64 channels per tap) still streams through a ring, one stage per tap.
+// Activation traffic drops from 9x to (TH+2)(TW+2)/(TH*TW) = 1.27x (16x16) per slab.
+//
+// Roles: the upper half of the waves sends all loads (see igemm_ws.hip for why), every wave
+// multiplies.  Two patch buffers alternate between slabs; the patch of slab kc+1 is requested
+// at the first tap of slab kc and, because loads retire in order, has landed by the time the
+// filter stage of its first tap has.
+//
+// Valid for stride 1, (R-1)*dil_h == 2 and (S-1)*dil_w == 2 (3x3 dilation 1 in particular),
+// source channels a multiple of 64.  The data gradient of such a layer is the same kind of
+// convolution over dy with displaced taps and the transposed filter [C][R][S][K].
+#include "common.h"
+#include "igemm.h"
+#include "dma.h"
+#include "igemm_epilogue.h"
+
+namespace sdconv {
+
+typedef _Float16 half8 __attribute__((ext_vector_type(8)));
+typedef float float16v __attribute__((ext_vector_type(16)));
+
+template <int MODE, int TH, int TW, int BN, int WGM, int WGN, int SB>
+__global__ __launch_bounds__(64 * WGM * WGN) void conv_patch_kernel(IgemmParams P)
+{
+    constexpr int EH = 2, EW = 2;                   // extra patch rows / columns
+    constexpr int PH = TH + EH, PW = TW + EW, PPX = PH * PW;
+    constexpr int NW = WGM * WGN, NI = NW / 2, IW0 = NW / 2;
+    constexpr int BM = TH * TW, WM = BM / WGM, WN = BN / WGN;
+    constexpr int FM = WM / 32, FN = WN / 32;
+    constexpr int NPL = (PPX + 8 * NI - 1) / (8 * NI);     // patch loads per fetching lane
+    constexpr int PATCHB = NPL * NI * 1024;                // bytes of one patch buffer
+    constexpr int PB = BN / (8 * NI);                      // filter loads per fetching lane and tap
+    constexpr int BSTAGE = BN * 128;
+    constexpr int D = SB - 1;                              // filter stages in flight
+    static_assert(NW % 2 == 0 && WM % 32 == 0 && WN % 32 == 0 && BN % (8 * NI) == 0, "tile shape");
+    static_assert(SB >= 2 && NPL + D * PB < 64, "loads in flight");   // vmcnt is a 6-bit counter
+
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+    const unsigned lds0 = (unsigned)(size_t)(__attribute__((address_space(3))) unsigned char*)smem;
+    unsigned char* bring = smem + 2 * PATCHB;
+    int* tap_bo = reinterpret_cast<int*>(bring + SB * BSTAGE);   // byte offset of the tap in a filter row
+    int* tap_po = tap_bo + kMaxTaps;                              // patch-pixel displacement of the tap
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+
+    // ---- which tile: runs of 8 consecutive tiles per XCD, runs interleaved over the XCDs ------
+    constexpr int kRun = 8;
+    const int xcd = blockIdx.x & 7, idx = blockIdx.x >> 3;
+    const int tile = ((idx / kRun) * 8 + xcd) * kRun + (idx % kRun);
+    if (tile >= P.total_tiles) return;
+    const int tn = tile % P.tiles_n;
+    int t2 = tile / P.tiles_n;
+    const int tx = t2 % P.tiles_w; t2 /= P.tiles_w;
+    const int ty = t2 % P.tiles_h;
+    const int n = t2 / P.tiles_h;
+    const int h0 = ty * TH, w0 = tx * TW, n0 = tn * BN;
+
+    // source pixel of output pixel (h, w) at tap (r, s): (h + oh, w + ow)
+    const int oh_min = (MODE == 0) ? -P.ph : P.ph - (P.R - 1) * P.dh;
+    const int ow_min = (MODE == 0) ? -P.pw : P.pw - (P.S - 1) * P.dw;
+    const int ntaps = P.R * P.S;
+    if (wave == 0 && lane < ntaps) {
+        const int r = lane / P.S, s = lane % P.S;
+        const int oh = (MODE == 0) ? r * P.dh - P.ph : P.ph - r * P.dh;
+        const int ow = (MODE == 0) ? s * P.dw - P.pw : P.pw - s * P.dw;
+        tap_bo[lane] = (r * P.S + s) * P.Cs * 2;
+        tap_po[lane] = (oh - oh_min) * PW + (ow - ow_min);
+    }
+    __syncthreads();
+    const int kchunks = P.Cs / 64;
+    const int nk = ntaps * kchunks;
+
+    // ---- fetching side ---------------------------------------------------------------------
+    const bool fetcher = wave >= IW0;
+    const int fw = wave - IW0;
+    const int fpix = lane >> 3, fslot = lane & 7;   // pixel (or filter row) within an instruction, chunk slot
+    unsigned a_off[NPL], b_off[PB];
+    if (fetcher) {
+#pragma unroll
+        for (int q = 0; q < NPL; ++q) {
+            const int pp = (q * NI + fw) * 8 + fpix;            // patch pixel this lane fetches
+            const int kcl = fslot ^ ((pp >> 1) & 7);            // logical chunk that lands in slot fslot
+            const int pr = pp / PW, pc = pp - pr * PW;
+            const int hs = h0 + oh_min + pr, ws = w0 + ow_min + pc;
+            const bool ok = pp < PPX && (unsigned)hs < (unsigned)P.Hs && (unsigned)ws < (unsigned)P.Ws;
+            a_off[q] = ok ? (unsigned)((((n * P.Hs + hs) * P.Ws + ws) * P.Cs + kcl * 8) * 2) : kOutOfRange;
+        }
+#pragma unroll
+        for (int p = 0; p < PB; ++p) {
+            const int row = (p * NI + fw) * 8 + fpix;
+            const int kcl = fslot ^ ((row >> 1) & 7);
+            const int nn = n0 + row;
+            b_off[p] = (nn < P.Cd) ? (unsigned)((nn * P.b_row_pitch + kcl * 8) * 2) : kOutOfRange;
+        }
+    }
+    const int4v rsrcA = make_rsrc(P.A, (unsigned)(P.NB * P.Hs * P.Ws * P.Cs) * 2u);
+    const int4v rsrcB = make_rsrc(P.B, (unsigned)(P.Cd * P.b_row_pitch) * 2u);
+
+    auto issue_patch = [&](int kc) {                // slab kc into buffer kc & 1
+        const unsigned soff = (unsigned)__builtin_amdgcn_readfirstlane(kc * 128);
+        const unsigned base = (unsigned)__builtin_amdgcn_readfirstlane((int)(lds0 + (kc & 1) * PATCHB + fw * 1024));
+#pragma unroll
+        for (int q = 0; q < NPL; ++q) dma16(a_off[q], rsrcA, soff, base + q * NI * 1024);
+    };
+    int nx_tap = 0, nx_kc = 0, nx_stage = 0;        // filter step the next issue_filter() fetches
+    auto issue_filter = [&]() {
+        const unsigned soff = (unsigned)__builtin_amdgcn_readfirstlane(tap_bo[nx_tap] + nx_kc * 128);
+        const unsigned base = (unsigned)__builtin_amdgcn_readfirstlane(
+            (int)(lds0 + 2 * PATCHB + nx_stage * BSTAGE + fw * 1024));
+#pragma unroll
+        for (int p = 0; p < PB; ++p) dma16(b_off[p], rsrcB, soff, base + p * NI * 1024);
+        const int t1 = nx_tap + 1;
+        const bool wrap = t1 == ntaps;
+        nx_tap = __builtin_amdgcn_readfirstlane(wrap ? 0 : t1);
+        nx_kc = __builtin_amdgcn_readfirstlane(wrap ? nx_kc + 1 : nx_kc);
+        nx_stage = __builtin_amdgcn_readfirstlane(nx_stage + 1 == SB ? 0 : nx_stage + 1);
+    };
+
+    // ---- multiplying side ------------------------------------------------------------------
+    const int wm = wave / WGN, wn = wave % WGN;
+    const int l32 = lane & 31, lhi = lane >> 5;
+    int pbase[FM];                                  // patch pixel of this lane's row at displacement 0
+#pragma unroll
+    for (int b = 0; b < FM; ++b) {
+        const int ml = wm * WM + b * 32 + l32;
+        pbase[b] = (ml / TW) * PW + (ml % TW);
+    }
+    float16v acc[FN][FM];
+#pragma unroll
+    for (int a = 0; a < FN; ++a)
+#pragma unroll
+        for (int b = 0; b < FM; ++b)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) acc[a][b][e] = 0.f;
+
+    auto compute = [&](int kc, int tap, int stage) {
+        const unsigned char* pa = smem + (kc & 1) * PATCHB;
+        const unsigned char* sb = bring + stage * BSTAGE;
+        const int po = __builtin_amdgcn_readfirstlane(tap_po[tap]);
+        int prow[FM];
+#pragma unroll
+        for (int b = 0; b < FM; ++b) prow[b] = pbase[b] + po;
+#pragma unroll
+        for (int kk = 0; kk < 4; ++kk) {
+            const int chunk = kk * 2 + lhi;
+            half8 fa[FM], fb[FN];
+#pragma unroll
+            for (int b = 0; b < FM; ++b)
+                fa[b] = *reinterpret_cast<const half8*>(pa + prow[b] * 128 + ((chunk ^ ((prow[b] >> 1) & 7)) << 4));
+#pragma unroll
+            for (int a = 0; a < FN; ++a) {
+                const int row = wn * WN + a * 32 + l32;
+                fb[a] = *reinterpret_cast<const half8*>(sb + row * 128 + ((chunk ^ ((row >> 1) & 7)) << 4));
+            }
+#pragma unroll
+            for (int a = 0; a < FN; ++a)
+#pragma unroll
+                for (int b = 0; b < FM; ++b)
+                    acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_f16(fb[a], fa[b], acc[a][b], 0, 0, 0);
+        }
+    };
+
+    // ---- pipeline: one step per (slab, tap), taps fastest ------------------------------------
+    if (fetcher) {
+        issue_patch(0);
+#pragma unroll
+        for (int s = 0; s < D; ++s)
+            if (s < nk) issue_filter();
+    }
+    int tap = 0, kc = 0, stage = 0;
+    for (int t = 0; t < nk; ++t) {
+        // loads retire in order: once the filter stage of step t is in, so is everything sent
+        // before it, in particular the patch of its slab (sent at least ntaps - D steps earlier)
+        // (the next slab's patch, sent at tap 0 between two filter stages, may stay in flight
+        // while it is younger than the stage awaited here)
+        if (fetcher) {
+            const bool patch_younger = tap >= 1 && tap <= D - 1 && kc + 1 < kchunks;
+            if (t + D - 1 >= nk) wait_vmcnt<0>();
+            else if (patch_younger) wait_vmcnt<(D - 1) * PB + NPL>();
+            else wait_vmcnt<(D - 1) * PB>();
+        }
+        __builtin_amdgcn_s_barrier();
+        if (fetcher) {
+            if (tap == 0 && kc + 1 < kchunks) issue_patch(kc + 1);   // its buffer was last read in slab kc-1
+            if (t + D < nk) issue_filter();
+        }
+        compute(kc, tap, stage);
+        stage = (stage + 1 == SB) ? 0 : stage + 1;
+        if (++tap == ntaps) { tap = 0; ++kc; }
+    }
+
+    // ---- epilogue ------------------------------------------------------------------------------
+    static_assert(NW * epilogue_strip_bytes<WN>() <= 2 * PATCHB, "epilogue strips fit in the patch buffers");
+    __builtin_amdgcn_s_barrier();                   // everybody is done reading the last patch
+    store_rows_via_lds<FM, FN>(acc, smem + wave * epilogue_strip_bytes<WN>(), lane, n0 + wn * WN, P,
+                               [&](int r) -> long {
+        const int ml = wm * WM + r;
+        const int h = h0 + ml / TW, w = w0 + ml % TW;
+        if (h >= P.Hd || w >= P.Wd) return -1;
+        return ((long)n * P.Hd + h) * P.Wd + w;
+    });
+}
+
+template <int MODE, int TH, int TW, int BN, int WGM, int WGN, int SB>
+static hipError_t launch_patch_variant(const IgemmParams& P, hipStream_t st)
+{
+    constexpr int NI = WGM * WGN / 2;
+    constexpr int NPL = ((TH + 2) * (TW + 2) + 8 * NI - 1) / (8 * NI);
+    constexpr size_t lds = (size_t)2 * NPL * NI * 1024 + (size_t)SB * BN * 128 + 2 * kMaxTaps * sizeof(int);
+    static_assert(lds <= 160 * 1024, "LDS budget");
+    static bool configured = false;
+    if (!configured) {
+        hipError_t e = hipFuncSetAttribute(
+            reinterpret_cast<const void*>(&conv_patch_kernel<MODE, TH, TW, BN, WGM, WGN, SB>),
+            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        if (e != hipSuccess) return e;
+        configured = true;
+    }
+    const int grid = ((P.total_tiles + 63) / 64) * 64;
+    hipLaunchKernelGGL((conv_patch_kernel<MODE, TH, TW, BN, WGM, WGN, SB>), dim3(grid), dim3(64 * WGM * WGN),
+                       lds, st, P);
+    return hipGetLastError();
+}
+
+const PatchVariant kPatchVariants[kNumPatchVariants] = {
+    {16, 16, 128, "conv_fwd_patch_16x16x128_s3", "conv_dgrad_patch_16x16x128_s3"},
+    {8, 16, 128, "conv_fwd_patch_8x16x128_s4", "conv_dgrad_patch_8x16x128_s4"},
+    {8, 16, 256, "conv_fwd_patch_8x16x256_s3", "conv_dgrad_patch_8x16x256_s3"},
+    {16, 16, 64, "conv_fwd_patch_16x16x64_s4", "conv_dgrad_patch_16x16x64_s4"},
+    {8, 32, 128, "conv_fwd_patch_8x32x128_s3", "conv_dgrad_patch_8x32x128_s3"},
+    {8, 16, 64, "conv_fwd_patch_8x16x64_s4", "conv_dgrad_patch_8x16x64_s4"},
+};
+
+#define SDCONV_PATCH_CASE(idx, TH, TW, BN, WGM, WGN, SB)                                      \
+    case 2 * (idx): return launch_patch_variant<0, TH, TW, BN, WGM, WGN, SB>(P, st);          \
+    case 2 * (idx) + 1: return launch_patch_variant<1, TH, TW, BN, WGM, WGN, SB>(P, st);
+
+hipError_t launch_conv_patch(int variant, const IgemmParams& P, hipStream_t st)
+{
+    const int key = variant * 2 + (P.mode ? 1 : 0);
+    switch (key) {
+        SDCONV_PATCH_CASE(0, 16, 16, 128, 4, 2, 3)
+        SDCONV_PATCH_CASE(1, 8, 16, 128, 2, 4, 4)
+        SDCONV_PATCH_CASE(2, 8, 16, 256, 2, 4, 3)
+        SDCONV_PATCH_CASE(3, 16, 16, 64, 4, 2, 4)
+        SDCONV_PATCH_CASE(4, 8, 32, 128, 4, 2, 3)
+        SDCONV_PATCH_CASE(5, 8, 16, 64, 4, 2, 4)
+        default: return hipErrorInvalidValue;
+    }
+}
+
+}  // namespace sdconv

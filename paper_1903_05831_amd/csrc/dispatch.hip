@@ -87,14 +87,32 @@ static const IgemmVariant& igemm_variant(int v)
     return v >= 100 ? kIgemmDmaVariants[v - 100] : kIgemmVariants[v];
 }
 
+// The patch kernels take stride-1 layers whose taps span exactly two extra rows and columns
+// (3x3, dilation 1) and whose contraction channels come in whole 64-channel slabs.
+static bool patch_ok(const Geom& g, bool dgrad)
+{
+    int cs = dgrad ? g.K : g.C;
+    return g.sh == 1 && g.sw == 1 && (g.R - 1) * g.dh == 2 && (g.S - 1) * g.dw == 2 && cs % 64 == 0 &&
+           g.R * g.S >= 4;
+}
+
+static const char* igemm_name(int v, bool dgrad)
+{
+    if (v >= 400) return dgrad ? kPatchVariants[v - 400].dgrad_name : kPatchVariants[v - 400].fwd_name;
+    return dgrad ? igemm_variant(v).dgrad_name : igemm_variant(v).fwd_name;
+}
+
 static int pick_variant(const Geom& g, bool dgrad)
 {
     int fv = forced_variant();
+    if (fv >= 400 && fv < 400 + kNumPatchVariants && patch_ok(g, dgrad)) return fv;
+    if (fv >= 400) fv = -1;
     if (fv >= 0 && fv < kNumIgemmVariants) return fv;
     if (fv >= 100 && fv < 100 + kNumIgemmDmaVariants) return fv;
     if (fv >= 300 && fv < 300 + kNumIgemmWsVariants) return fv;
     if (fv >= 200 && fv < 200 + kNumIgemmPersVariants && g.R * g.S * (dgrad ? g.sh * g.sw : 1) <= 1024) return fv;
-    if (const TunedEntry* e = tuned_lookup(g, dgrad ? SDCONV_DGRAD : SDCONV_FWD)) return e->variant;
+    if (const TunedEntry* e = tuned_lookup(g, dgrad ? SDCONV_DGRAD : SDCONV_FWD))
+        if (e->variant < 400 || patch_ok(g, dgrad)) return e->variant;
     int nout = dgrad ? g.C : g.K;
     int kgemm = g.R * g.S * (dgrad ? g.K : g.C);
     int starts[kMaxClasses + 1], nc;
@@ -113,7 +131,7 @@ Plan plan_fwd(const Geom& g)
     if (thin_ok(g)) return Plan{ROUTE_THIN, 0, 1, align256(thin_packed_filter_bytes(g)), "thin_fwd"};
     if (!igemm_ok(g)) return Plan{ROUTE_DIRECT, 0, 1, 0, "direct_fwd"};
     int v = pick_variant(g, false);
-    return Plan{ROUTE_IGEMM, v, 1, 0, igemm_variant(v).fwd_name};
+    return Plan{ROUTE_IGEMM, v, 1, 0, igemm_name(v, false)};
 }
 
 Plan plan_dgrad(const Geom& g)
@@ -126,7 +144,7 @@ Plan plan_dgrad(const Geom& g)
     if (!igemm_ok(g) || g.sh * g.sw > kMaxClasses) return Plan{ROUTE_DIRECT, 0, 1, 0, "direct_dgrad"};
     int v = pick_variant(g, true);
     size_t ws = align256((size_t)g.K * g.R * g.S * g.C * sizeof(__half));
-    return Plan{ROUTE_IGEMM, v, 1, ws, igemm_variant(v).dgrad_name};
+    return Plan{ROUTE_IGEMM, v, 1, ws, igemm_name(v, true)};
 }
 
 // Pixel-range count for the weight gradient: enough workgroups to fill the chip a few times
@@ -186,6 +204,19 @@ static hipError_t run_igemm(const Geom& g, const Plan& p, bool dgrad, const __ha
     P.sh = g.sh; P.sw = g.sw; P.ph = g.ph; P.pw = g.pw; P.dh = g.dh; P.dw = g.dw;
     P.mode = dgrad ? 1 : 0;
     P.sw_cls = dgrad ? g.sw : 1;
+    P.b_row_pitch = g.R * g.S * P.Cs;
+    P.tiles_h = P.tiles_w = 0;
+    if (p.variant >= 400) {
+        const PatchVariant& pv = kPatchVariants[p.variant - 400];
+        P.nclasses = 1;
+        P.class_tile_start[0] = 0;
+        P.tiles_h = (P.Hd + pv.th - 1) / pv.th;
+        P.tiles_w = (P.Wd + pv.tw - 1) / pv.tw;
+        P.tiles_n = (P.Cd + pv.bn - 1) / pv.bn;
+        P.total_tiles = P.NB * P.tiles_h * P.tiles_w * P.tiles_n;
+        P.class_tile_start[1] = P.total_tiles;
+        return launch_conv_patch(p.variant - 400, P, st);
+    }
     const IgemmVariant& v = igemm_variant(p.variant);
     int tiles_m = row_tiles(g, dgrad, v.bm, P.class_tile_start, &P.nclasses);
     P.tiles_n = (P.Cd + v.bn - 1) / v.bn;

@@ -23,6 +23,7 @@ struct IgemmParams {
     int total_tiles;   // row tiles (all classes) x column tiles
     int b_row_pitch;   // R*S*Cs
     int class_tile_start[kMaxClasses + 1];   // first row-tile of each class, then the total
+    int tiles_h, tiles_w;   // spatial tiles per image (patch kernels only)
 };
 
 struct IgemmVariant { int bm, bn; const char* fwd_name; const char* dgrad_name; };
@@ -35,9 +36,13 @@ hipError_t launch_igemm_dma(int variant, const IgemmParams& P, hipStream_t st);
 constexpr int kNumIgemmPersVariants = 10;
 extern const IgemmVariant kIgemmPersVariants[kNumIgemmPersVariants];
 hipError_t launch_igemm_pers(int variant, const IgemmParams& P, hipStream_t st);
-constexpr int kNumIgemmWsVariants = 12;
+constexpr int kNumIgemmWsVariants = 10;
 extern const IgemmVariant kIgemmWsVariants[kNumIgemmWsVariants];
 hipError_t launch_igemm_ws(int variant, const IgemmParams& P, hipStream_t st);
+struct PatchVariant { int th, tw, bn; const char* fwd_name; const char* dgrad_name; };
+constexpr int kNumPatchVariants = 6;
+extern const PatchVariant kPatchVariants[kNumPatchVariants];
+hipError_t launch_conv_patch(int variant, const IgemmParams& P, hipStream_t st);
 hipError_t launch_igemm(int variant, const IgemmParams& P, int total_tiles, hipStream_t st);
 hipError_t launch_filter_transpose(const __half* w, __half* wT, int K, int RS, int C, hipStream_t st);
 

@@ -19,11 +19,11 @@ template <int WN> constexpr int epilogue_strip_bytes() { return 32 * (WN * 2 + 1
 // acc[a][b]: block (rows b*32.., columns a*32..) of the wave's WM x WN sub-tile.
 // strip: this wave's private LDS area of epilogue_strip_bytes<WN>() bytes; the caller has made
 // sure (workgroup barrier) that nobody still reads what the strip overwrites.
-// m_base/col_base: first GEMM row / destination channel of the wave's sub-tile.
-template <int FM, int FN, typename Acc>
-__device__ __forceinline__ void store_tile_via_lds(Acc (&acc)[FN][FM], unsigned char* strip, int lane,
-                                                   int m_base, int col_base, int Mcls, const IgemmParams& P,
-                                                   int Hi, int Wj, int eh, int ew, int ca, int cb)
+// pix_of(r): destination pixel index (n*Hd + h)*Wd + w of row r of the wave's sub-tile, or a
+// negative value for rows that have no destination.  col_base: first destination channel.
+template <int FM, int FN, typename Acc, typename PixOf>
+__device__ __forceinline__ void store_rows_via_lds(Acc (&acc)[FN][FM], unsigned char* strip, int lane,
+                                                   int col_base, const IgemmParams& P, PixOf pix_of)
 {
     typedef _Float16 h4 __attribute__((ext_vector_type(4)));
     typedef _Float16 h8 __attribute__((ext_vector_type(8)));
@@ -33,7 +33,6 @@ __device__ __forceinline__ void store_tile_via_lds(Acc (&acc)[FN][FM], unsigned 
     constexpr int PITCH = WN * 2 + 16;
     const int l32 = lane & 31, lhi = lane >> 5;
     const int srow = lane / CW, schunk = lane % CW;
-    const bool linear = (eh == 1 && ew == 1);       // destination pixel index == GEMM row index
 #pragma unroll
     for (int b = 0; b < FM; ++b) {
 #pragma unroll
@@ -53,21 +52,30 @@ __device__ __forceinline__ void store_tile_via_lds(Acc (&acc)[FN][FM], unsigned 
         for (int j = 0; j < 32 / RPI; ++j) {
             const int r = j * RPI + srow;
             h8 v = *reinterpret_cast<const h8*>(strip + r * PITCH + schunk * 16);
-            const int m = m_base + b * 32 + r;
             const int col = col_base + schunk * 8;
-            if (m < Mcls && col < P.Cd) {
-                long pix;
-                if (linear) pix = m;
-                else {
-                    int n = m / (Hi * Wj);
-                    int rem = m - n * (Hi * Wj);
-                    int i = rem / Wj, jj = rem - i * Wj;
-                    pix = ((long)n * P.Hd + (i * eh + ca)) * P.Wd + (jj * ew + cb);
-                }
-                *reinterpret_cast<h8*>(P.D + pix * P.Cd + col) = v;
-            }
+            const long pix = pix_of(b * 32 + r);
+            if (pix >= 0 && col < P.Cd) *reinterpret_cast<h8*>(P.D + pix * P.Cd + col) = v;
         }
     }
+}
+
+// Rows are GEMM rows m_base.. of an implicit-GEMM tile (pixels of one stride-parity class in
+// (n, i, j) order; eh/ew/ca/cb place class pixel (i, j) at (i*eh + ca, j*ew + cb)).
+template <int FM, int FN, typename Acc>
+__device__ __forceinline__ void store_tile_via_lds(Acc (&acc)[FN][FM], unsigned char* strip, int lane,
+                                                   int m_base, int col_base, int Mcls, const IgemmParams& P,
+                                                   int Hi, int Wj, int eh, int ew, int ca, int cb)
+{
+    const bool linear = (eh == 1 && ew == 1);       // destination pixel index == GEMM row index
+    store_rows_via_lds<FM, FN>(acc, strip, lane, col_base, P, [&](int r) -> long {
+        const int m = m_base + r;
+        if (m >= Mcls) return -1;
+        if (linear) return m;
+        int n = m / (Hi * Wj);
+        int rem = m - n * (Hi * Wj);
+        int i = rem / Wj, jj = rem - i * Wj;
+        return ((long)n * P.Hd + (i * eh + ca)) * P.Wd + (jj * ew + cb);
+    });
 }
 
 }  // namespace sdconv

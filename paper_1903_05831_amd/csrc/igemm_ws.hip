@@ -304,8 +304,6 @@ const IgemmVariant kIgemmWsVariants[kNumIgemmWsVariants] = {
     {128, 64, "igemm_fwd_ws_128x64x64_4w2f_s4", "igemm_dgrad_ws_128x64x64_4w2f_s4"},
     {128, 64, "igemm_fwd_ws_128x64x64_8w0f_s4", "igemm_dgrad_ws_128x64x64_8w0f_s4"},
     {128, 256, "igemm_fwd_ws_128x256x64_8w0f_s3", "igemm_dgrad_ws_128x256x64_8w0f_s3"},
-    {224, 256, "igemm_fwd_ws_224x256x64_8w0f_s2", "igemm_dgrad_ws_224x256x64_8w0f_s2"},
-    {256, 256, "igemm_fwd_ws_256x256x64_8w0f_s2_1x8", "igemm_dgrad_ws_256x256x64_8w0f_s2_1x8"},
 };
 
 #define SDCONV_WS_CASE(idx, BM, BN, WGM, WGN, S, BK, NP)                                      \
@@ -326,8 +324,6 @@ hipError_t launch_igemm_ws(int variant, const IgemmParams& P, hipStream_t st)
         SDCONV_WS_CASE(7, 128, 64, 2, 2, 4, 64, 2)
         SDCONV_WS_CASE(8, 128, 64, 4, 2, 4, 64, 0)
         SDCONV_WS_CASE(9, 128, 256, 2, 4, 3, 64, 0)
-        SDCONV_WS_CASE(10, 224, 256, 1, 8, 2, 64, 0)
-        SDCONV_WS_CASE(11, 256, 256, 1, 8, 2, 64, 0)
         default: return hipErrorInvalidValue;
     }
 }

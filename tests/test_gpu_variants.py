@@ -1,0 +1,83 @@
+"""GPU parity of every tile variant of the pipelined kernels, forced one by one through the
+dispatcher's environment hooks (read per call), against the fp64 CPU oracle on full tensors.
+The shapes give ragged row / spatial tiles, several images, filter-count tails and more than
+one 64-channel slab, so every variant sees partial tiles on each axis."""
+import os
+
+import numpy as np
+import pytest
+
+import paper_1903_05831_amd as sd
+
+from gpu_harness import check_all_passes, say
+
+pytestmark = pytest.mark.gpu
+
+
+def _rand_case(N, H, W, C, K, R, S, stride, pad, dil, seed):
+    d = sd.make_desc(N, H, W, C, K, R, S, stride, pad, dil)
+    ho, wo = sd.conv2d_out_shape(d)
+    rng = np.random.default_rng(seed)
+    x = rng.standard_normal((N, H, W, C), dtype=np.float32).astype(np.float16)
+    w = (rng.standard_normal((K, R, S, C), dtype=np.float32) * np.float32(np.sqrt(2.0 / (R * S * C)))).astype(np.float16)
+    g = rng.standard_normal((N, ho, wo, K), dtype=np.float32).astype(np.float16)
+    return d, x, w, g
+
+
+class forced:
+    def __init__(self, **env):
+        self.env = {k: str(v) for k, v in env.items()}
+
+    def __enter__(self):
+        self.old = {k: os.environ.get(k) for k in self.env}
+        os.environ.update(self.env)
+
+    def __exit__(self, *exc):
+        for k, v in self.old.items():
+            if v is None:
+                os.environ.pop(k, None)
+            else:
+                os.environ[k] = v
+
+
+# stride-1 layers the patch kernels accept (taps span two extra rows and columns, contraction
+# channels in whole 64-channel slabs on both the forward and the data-gradient side)
+PATCH_SHAPES = [
+    # N  H   W   C    K   R  S  stride  pad     dil
+    (2, 21, 37, 64, 64, 3, 3, (1, 1), (1, 1), (1, 1)),      # ragged tiles both ways, two images
+    (1, 19, 18, 128, 192, 3, 3, (1, 1), (1, 1), (1, 1)),    # two slabs, filter tail (192 = 128 + 64)
+    (1, 17, 33, 64, 128, 3, 3, (1, 1), (0, 0), (1, 1)),     # no padding: output smaller than input
+    (1, 12, 20, 64, 64, 3, 3, (1, 1), (2, 2), (1, 1)),      # padding 2: output larger than input
+    (1, 16, 16, 64, 64, 2, 2, (1, 1), (1, 1), (2, 2)),      # 2x2 taps, dilation 2
+    (1, 9, 40, 64, 64, 3, 2, (1, 1), (1, 1), (1, 2)),       # 3x2 taps, dilation 1x2
+]
+PATCH_VARIANTS = [400, 401, 402, 403, 404, 405]
+
+
+@pytest.mark.parametrize("variant", PATCH_VARIANTS)
+def test_patch_kernel_variants(variant):
+    for case in PATCH_SHAPES:
+        say(f"patch variant {variant} case {case}")
+        d, x, w, g = _rand_case(*case, seed=variant * 31 + len(case))
+        with forced(SDCONV_IGEMM_VARIANT=variant, SDCONV_NO_TUNED_TABLE=1):
+            assert "patch" in sd.kernel_name(d, sd.FWD), "shape must reach the patch kernel"
+            assert "patch" in sd.kernel_name(d, sd.DGRAD)
+            check_all_passes(d, x, w, g, f"patch{variant}{case}")
+
+
+WS_SHAPES = [
+    (2, 23, 29, 64, 72, 3, 3, (2, 2), (1, 1), (1, 1)),      # strided: parity classes in the data gradient
+    (1, 31, 37, 136, 200, 3, 3, (1, 1), (1, 1), (1, 1)),    # short last channel slab, filter tail
+    (1, 31, 37, 128, 264, 1, 1, (1, 1), (0, 0), (1, 1)),    # 1x1, more than one 256-wide column tile
+]
+WS_VARIANTS = list(range(300, 310))
+
+
+@pytest.mark.parametrize("variant", WS_VARIANTS)
+def test_split_role_kernel_variants(variant):
+    for case in WS_SHAPES:
+        say(f"ws variant {variant} case {case}")
+        d, x, w, g = _rand_case(*case, seed=variant * 17 + 3)
+        with forced(SDCONV_IGEMM_VARIANT=variant, SDCONV_NO_TUNED_TABLE=1):
+            assert "_ws_" in sd.kernel_name(d, sd.FWD)
+            check_all_passes(d, x, w, g, f"ws{variant}{case}")
