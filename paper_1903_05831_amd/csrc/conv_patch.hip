@@ -16,11 +16,13 @@
 //
 // Valid for stride 1, (R-1)*dil_h == 2 and (S-1)*dil_w == 2 (3x3 dilation 1 in particular),
 // source channels a multiple of 64.  The data gradient of such a layer is the same kind of
-// convolution over dy with displaced taps and the transposed filter [C][R][S][K].
+// convolution over dy with displaced taps; it reads the filter as stored, [K][R][S][C], as
+// 64-filter x BN-channel tiles that the transposing LDS read turns into fragments (lds_tr.h).
 #include "common.h"
 #include "igemm.h"
 #include "dma.h"
 #include "igemm_epilogue.h"
+#include "lds_tr.h"
 
 namespace sdconv {
 
@@ -73,7 +75,7 @@ __global__ __launch_bounds__(64 * WGM * WGN) void conv_patch_kernel(IgemmParams 
         const int r = lane / P.S, s = lane % P.S;
         const int oh = (MODE == 0) ? r * P.dh - P.ph : P.ph - r * P.dh;
         const int ow = (MODE == 0) ? s * P.dw - P.pw : P.pw - s * P.dw;
-        tap_bo[lane] = (r * P.S + s) * P.Cs * 2;
+        tap_bo[lane] = (r * P.S + s) * (MODE == 0 ? P.Cs : P.Cd) * 2;
         tap_po[lane] = (oh - oh_min) * PW + (ow - ow_min);
     }
     __syncthreads();
@@ -97,14 +99,22 @@ __global__ __launch_bounds__(64 * WGM * WGN) void conv_patch_kernel(IgemmParams 
         }
 #pragma unroll
         for (int p = 0; p < PB; ++p) {
-            const int row = (p * NI + fw) * 8 + fpix;
-            const int kcl = fslot ^ ((row >> 1) & 7);
-            const int nn = n0 + row;
-            b_off[p] = (nn < P.Cd) ? (unsigned)((nn * P.b_row_pitch + kcl * 8) * 2) : kOutOfRange;
+            if (MODE == 0) {
+                const int row = (p * NI + fw) * 8 + fpix;
+                const int kcl = fslot ^ ((row >> 1) & 7);
+                const int nn = n0 + row;
+                b_off[p] = (nn < P.Cd) ? (unsigned)((nn * P.b_row_pitch + kcl * 8) * 2) : kOutOfRange;
+            } else {
+                // [64 filters][BN channels]: chunk slot (p*NI + fw)*64 + lane of the stage
+                const int slot = (p * NI + fw) * 64 + lane;
+                const int krow = slot / (BN / 8), pc = slot % (BN / 8);
+                const int c = n0 + swizzled_chunk<BN>(krow, pc) * 8;
+                b_off[p] = (c < P.Cd) ? (unsigned)((krow * P.b_row_pitch + c) * 2) : kOutOfRange;
+            }
         }
     }
     const int4v rsrcA = make_rsrc(P.A, (unsigned)(P.NB * P.Hs * P.Ws * P.Cs) * 2u);
-    const int4v rsrcB = make_rsrc(P.B, (unsigned)(P.Cd * P.b_row_pitch) * 2u);
+    const int4v rsrcB = make_rsrc(P.B, (unsigned)((MODE == 0 ? P.Cd : P.Cs) * P.b_row_pitch) * 2u);
 
     auto issue_patch = [&](int kc) {                // slab kc into buffer kc & 1
         const unsigned soff = (unsigned)__builtin_amdgcn_readfirstlane(kc * 128);
@@ -114,7 +124,8 @@ __global__ __launch_bounds__(64 * WGM * WGN) void conv_patch_kernel(IgemmParams 
     };
     int nx_tap = 0, nx_kc = 0, nx_stage = 0;        // filter step the next issue_filter() fetches
     auto issue_filter = [&]() {
-        const unsigned soff = (unsigned)__builtin_amdgcn_readfirstlane(tap_bo[nx_tap] + nx_kc * 128);
+        const unsigned soff = (unsigned)__builtin_amdgcn_readfirstlane(
+            tap_bo[nx_tap] + (MODE == 0 ? nx_kc * 128 : nx_kc * 64 * P.b_row_pitch * 2));
         const unsigned base = (unsigned)__builtin_amdgcn_readfirstlane(
             (int)(lds0 + 2 * PATCHB + nx_stage * BSTAGE + fw * 1024));
 #pragma unroll
@@ -159,8 +170,12 @@ __global__ __launch_bounds__(64 * WGM * WGN) void conv_patch_kernel(IgemmParams 
                 fa[b] = *reinterpret_cast<const half8*>(pa + prow[b] * 128 + ((chunk ^ ((prow[b] >> 1) & 7)) << 4));
 #pragma unroll
             for (int a = 0; a < FN; ++a) {
-                const int row = wn * WN + a * 32 + l32;
-                fb[a] = *reinterpret_cast<const half8*>(sb + row * 128 + ((chunk ^ ((row >> 1) & 7)) << 4));
+                if (MODE == 0) {
+                    const int row = wn * WN + a * 32 + l32;
+                    fb[a] = *reinterpret_cast<const half8*>(sb + row * 128 + ((chunk ^ ((row >> 1) & 7)) << 4));
+                } else {
+                    fb[a] = lds_frag_tr<BN>(sb, kk * 16, wn * WN + a * 32, lane);
+                }
             }
 #pragma unroll
             for (int a = 0; a < FN; ++a)

@@ -143,7 +143,9 @@ Plan plan_dgrad(const Geom& g)
         return Plan{ROUTE_THIN, 0, 1, align256((size_t)g.K * g.R * g.S * g.C * sizeof(__half)), "thin_dgrad"};
     if (!igemm_ok(g) || g.sh * g.sw > kMaxClasses) return Plan{ROUTE_DIRECT, 0, 1, 0, "direct_dgrad"};
     int v = pick_variant(g, true);
-    size_t ws = align256((size_t)g.K * g.R * g.S * g.C * sizeof(__half));
+    // the older kernels want the filter transposed to [C][R][S][K] in the workspace; the
+    // split-role and patch kernels read it as stored
+    size_t ws = v >= 300 ? 0 : align256((size_t)g.K * g.R * g.S * g.C * sizeof(__half));
     return Plan{ROUTE_IGEMM, v, 1, ws, igemm_name(v, true)};
 }
 
@@ -204,7 +206,10 @@ static hipError_t run_igemm(const Geom& g, const Plan& p, bool dgrad, const __ha
     P.sh = g.sh; P.sw = g.sw; P.ph = g.ph; P.pw = g.pw; P.dh = g.dh; P.dw = g.dw;
     P.mode = dgrad ? 1 : 0;
     P.sw_cls = dgrad ? g.sw : 1;
-    P.b_row_pitch = g.R * g.S * P.Cs;
+    // elements between consecutive rows of the filter matrix the kernel reads: [Cd][R][S][Cs]
+    // (forward, and the transposed copy of the older data-gradient kernels), or the filter as
+    // stored, [K = Cs][R][S][C = Cd], for the data gradient of the split-role and patch kernels
+    P.b_row_pitch = g.R * g.S * ((dgrad && p.variant >= 300) ? P.Cd : P.Cs);
     P.tiles_h = P.tiles_w = 0;
     if (p.variant >= 400) {
         const PatchVariant& pv = kPatchVariants[p.variant - 400];
@@ -221,7 +226,6 @@ static hipError_t run_igemm(const Geom& g, const Plan& p, bool dgrad, const __ha
     int tiles_m = row_tiles(g, dgrad, v.bm, P.class_tile_start, &P.nclasses);
     P.tiles_n = (P.Cd + v.bn - 1) / v.bn;
     P.total_tiles = tiles_m * P.tiles_n;
-    P.b_row_pitch = g.R * g.S * P.Cs;
     if (p.variant >= 300) return launch_igemm_ws(p.variant - 300, P, st);
     if (p.variant >= 200) return launch_igemm_pers(p.variant - 200, P, st);
     if (p.variant >= 100) return launch_igemm_dma(p.variant - 100, P, st);
@@ -239,6 +243,7 @@ hipError_t run_dgrad(const Geom& g, const Plan& p, const __half* dy, const __hal
 {
     if (p.route == ROUTE_DIRECT) return launch_direct_dgrad(g, dy, w, dx, st);
     if (p.route == ROUTE_THIN && p.variant == 1) return launch_thin_dgrad_mfma(g, dy, w, dx, ws, st);
+    if (p.route == ROUTE_IGEMM && p.variant >= 300) return run_igemm(g, p, true, dy, w, dx, st);
     __half* wT = static_cast<__half*>(ws);
     hipError_t e = launch_filter_transpose(w, wT, g.K, g.R * g.S, g.C, st);
     if (e != hipSuccess) return e;

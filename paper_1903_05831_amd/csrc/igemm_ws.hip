@@ -12,6 +12,11 @@
 //            is stalled in its burst of loads, then the upper one multiplies.
 // One workgroup barrier per contraction step, shared by both kinds of wave, orders the ring.
 //
+// The data gradient (MODE 1) reads the filter as it is stored, [K][R][S][C]: its B tile is 64
+// filters (contraction rows) x BN input channels, kept in LDS in that orientation and turned
+// into fragments by the transposing LDS read (lds_tr.h), so no transposed copy of the filter
+// is needed.  The forward pass keeps the [row][64 contraction halves] tiles of igemm_dma.hip.
+//
 // Row addressing is computed once per workgroup by all threads (one tile row each: byte offset
 // of the pixel at tap displacement 0 and a bit mask of the taps inside the image) and handed to
 // the fetching waves through LDS.
@@ -19,6 +24,7 @@
 #include "igemm.h"
 #include "dma.h"
 #include "igemm_epilogue.h"
+#include "lds_tr.h"
 
 namespace sdconv {
 
@@ -45,6 +51,7 @@ __global__ __launch_bounds__(64 * (WGM * WGN + NP)) void igemm_ws_kernel(IgemmPa
     static_assert(WM % 32 == 0 && WN % 32 == 0 && BM % RPP == 0 && BN % RPP == 0, "tile shape");
     static_assert(S >= 2 && INFLIGHT < 64, "pipeline depth");
     static_assert(BK == 64 || BK == 32, "contraction step");
+    static_assert(MODE == 0 || (BK == 64 && (64 * NI) % (BN / 8) == 0), "data-gradient filter tile");
     static_assert(NI >= 1 && (NP > 0 || NWC % 2 == 0), "fetching waves");
 
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
@@ -100,7 +107,7 @@ __global__ __launch_bounds__(64 * (WGM * WGN + NP)) void igemm_ws_kernel(IgemmPa
         int pos = __popcll(mask & ((1ull << lane) - 1ull));
         if (ok) {
             tap_oh[pos] = oh; tap_ow[pos] = ow;
-            tap_bo[pos] = (r * P.S + s) * P.Cs * 2;
+            tap_bo[pos] = (r * P.S + s) * (MODE == 0 ? P.Cs : P.Cd) * 2;
             tap_ad[pos] = (oh * P.Ws + ow) * P.Cs * 2;
         }
         if (lane == 0) tap_cnt[0] = __popcll(mask);
@@ -141,6 +148,7 @@ __global__ __launch_bounds__(64 * (WGM * WGN + NP)) void igemm_ws_kernel(IgemmPa
     unsigned a_off[PA];
     unsigned long long a_mask[PA];
     unsigned b_off[PB];
+    int b_krow[PB];                                 // MODE 1: filter (contraction row) of each load
     const bool partial = (P.Cs % BK) != 0;          // last channel chunk is short
     if (fetcher) {
 #pragma unroll
@@ -152,14 +160,23 @@ __global__ __launch_bounds__(64 * (WGM * WGN + NP)) void igemm_ws_kernel(IgemmPa
         }
 #pragma unroll
         for (int p = 0; p < PB; ++p) {
-            const int r = lrow + RPP * p;
-            const int kcl = kc ^ ((r >> SWS) & (CPR - 1));
-            const int n = n0 + r;
-            b_off[p] = (n < P.Cd) ? (unsigned)((n * P.b_row_pitch + kcl * 8) * 2) : kOutOfRange;
+            if (MODE == 0) {
+                const int r = lrow + RPP * p;
+                const int kcl = kc ^ ((r >> SWS) & (CPR - 1));
+                const int n = n0 + r;
+                b_off[p] = (n < P.Cd) ? (unsigned)((n * P.b_row_pitch + kcl * 8) * 2) : kOutOfRange;
+            } else {
+                // [64 filters][BN channels]: chunk slot (p*64*NI + ft) of the stage
+                const int slot = p * 64 * NI + ft;
+                const int krow = slot / (BN / 8), pc = slot % (BN / 8);
+                const int c = n0 + swizzled_chunk<BN>(krow, pc) * 8;
+                b_krow[p] = krow;
+                b_off[p] = (c < P.Cd) ? (unsigned)((krow * P.b_row_pitch + c) * 2) : kOutOfRange;
+            }
         }
     }
     const int4v rsrcA = make_rsrc(P.A, (unsigned)(P.NB * P.Hs * P.Ws * P.Cs) * 2u);
-    const int4v rsrcB = make_rsrc(P.B, (unsigned)(P.Cd * P.b_row_pitch) * 2u);
+    const int4v rsrcB = make_rsrc(P.B, (unsigned)((MODE == 0 ? P.Cd : P.Cs) * P.b_row_pitch) * 2u);
 
     int nx_tap = 0, nx_kc = 0;          // contraction step the next issue() fetches (wave-uniform)
     auto issue = [&](int stage) {
@@ -177,12 +194,22 @@ __global__ __launch_bounds__(64 * (WGM * WGN + NP)) void igemm_ws_kernel(IgemmPa
             unsigned voff = ok ? a_off[p] + ad : kOutOfRange;
             dma16(voff, rsrcA, cbytes, sbase + p * RPP * ROWB);
         }
+        if (MODE == 0) {
 #pragma unroll
-        for (int p = 0; p < PB; ++p) {
-            const int r = lrow + RPP * p;
-            const int kcl = kc ^ ((r >> SWS) & (CPR - 1));
-            unsigned voff = (partial && kcl * 8 >= cleft) ? kOutOfRange : b_off[p];
-            dma16(voff, rsrcB, bo + cbytes, sbase + BM * ROWB + p * RPP * ROWB);
+            for (int p = 0; p < PB; ++p) {
+                const int r = lrow + RPP * p;
+                const int kcl = kc ^ ((r >> SWS) & (CPR - 1));
+                unsigned voff = (partial && kcl * 8 >= cleft) ? kOutOfRange : b_off[p];
+                dma16(voff, rsrcB, bo + cbytes, sbase + BM * ROWB + p * RPP * ROWB);
+            }
+        } else {
+            // filters nx_kc*64 .. +63 of tap nx_tap, BN channels each
+            const unsigned kbytes = (unsigned)__builtin_amdgcn_readfirstlane(nx_kc * BK * P.b_row_pitch * 2);
+#pragma unroll
+            for (int p = 0; p < PB; ++p) {
+                unsigned voff = (partial && b_krow[p] >= cleft) ? kOutOfRange : b_off[p];
+                dma16(voff, rsrcB, bo + kbytes, sbase + BM * ROWB + p * NI * 1024);
+            }
         }
         // taps vary fastest: the taps of a 3x3 re-read nearly the same pixels of one channel
         // slab back to back, while it is still in L2
@@ -231,8 +258,12 @@ __global__ __launch_bounds__(64 * (WGM * WGN + NP)) void igemm_ws_kernel(IgemmPa
             }
 #pragma unroll
             for (int a = 0; a < FN; ++a) {
-                int row = wn * WN + a * 32 + l32;
-                fb[a] = *reinterpret_cast<const half8*>(sb + row * ROWB + ((chunk ^ ((row >> SWS) & (CPR - 1))) << 4));
+                if (MODE == 0) {
+                    int row = wn * WN + a * 32 + l32;
+                    fb[a] = *reinterpret_cast<const half8*>(sb + row * ROWB + ((chunk ^ ((row >> SWS) & (CPR - 1))) << 4));
+                } else {
+                    fb[a] = lds_frag_tr<BN>(sb, kk * 16, wn * WN + a * 32, lane);
+                }
             }
 #pragma unroll
             for (int a = 0; a < FN; ++a)

@@ -21,30 +21,13 @@
 #include "wgrad.h"
 #include "dma.h"
 
+#include "lds_tr.h"
+
 namespace sdconv {
 
 typedef _Float16 half8 __attribute__((ext_vector_type(8)));
 typedef _Float16 half4 __attribute__((ext_vector_type(4)));
-typedef short short4v __attribute__((ext_vector_type(4)));
 typedef float float16v __attribute__((ext_vector_type(16)));
-
-__device__ __forceinline__ half4 lds_read_tr16(const unsigned char* p)
-{
-    typedef __attribute__((address_space(3))) short4v* lds_ptr;
-    short4v v = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr)(p));
-    return __builtin_bit_cast(half4, v);
-}
-
-// Byte offset of (row, col half-index) in a [rows][BW halves] tile with swizzled granules.
-template <int BW>
-__device__ __forceinline__ int sw_off(int row, int col)
-{
-    constexpr int pitch = BW * 2;
-    constexpr int gmask = (pitch >= 256) ? 3 : (pitch / 64 - 1);
-    int byte = col * 2;
-    int gran = (byte >> 6) ^ (row & gmask);
-    return row * pitch + (gran << 6) + (byte & 63);
-}
 
 template <int BM, int BN, int WGM, int WGN, int S, int BP, bool LINEAR>
 __global__ __launch_bounds__(64 * WGM * WGN) void wgrad_dma_kernel(WgradParams P)
