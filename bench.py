@@ -6,9 +6,9 @@ workload (N=2 images of 800x1344 plus 512 RoIs; 53 conv layers), in the order of
 step: conv2d_fwd for every layer first to last, then last to first conv2d_dgrad and
 conv2d_wgrad of each layer, then grad_unscale_check over all 23 454 912 fp32 weight-gradient
 elements.  The two gradients of a layer depend only on the incoming gradient, not on each
-other: with --streams 2 (default) the weight gradients go to a second HIP stream (default
-priority, own workspace) and overlap the data gradients; --streams 1 keeps everything on one
-stream.  Inputs are synthetic (N(0,1) activations and gradients, He-normal weights), generated
+other: with --streams 2 (default) the weight gradients (and the projection shortcuts) go to a
+second HIP stream (default priority, own workspace), each gated by an event so that it starts
+only when the gradient it consumes exists; --streams 1 keeps everything on one stream.  Inputs are synthetic (N(0,1) activations and gradients, He-normal weights), generated
 on the device before the timed region.
 
 Prints ONE JSON line.  `value` is algorithmic TFLOP/s of the whole step (2*N*Ho*Wo*K*R*S*C
@@ -117,17 +117,66 @@ def main() -> int:
     def unscale():
         sd.grad_unscale_check(dw_flat, dw_total, inv_scale, flag, stream)
 
+    # Schedule of one step on two streams, with the dependencies a training step has:
+    #  - forward: the projection shortcut (".0p") of a stage's first block only needs the block
+    #    input, so it runs on the side stream next to the 0a-0b-0c branch; the next block waits
+    #    for both;
+    #  - backward: a layer's weight gradient needs the gradient of the layer's output, which the
+    #    data gradient issued just before it on the main stream produces: an event recorded
+    #    there gates the side stream, so wgrad(l) runs beside dgrad(l) and never before its
+    #    input exists.  The shortcut's two gradients run on the side stream; the layer before
+    #    the block waits for both branches.
+    n_l = len(jobs)
+    fwd_calls = calls[:n_l]
+    bwd_calls = calls[n_l:]             # dgrad, wgrad pairs, last layer first
+    ev_pool = [torch.cuda.Event() for _ in range(2 * n_l + 16)] if side_stream is not None else []
+
     def step():
-        for c in calls:
-            if c[1] == "wgrad":
-                c[4](ws2, stream2)
-            else:
+        if side_stream is None:
+            for c in calls:
                 c[4](ws, stream)
-        if side_stream is not None:
-            main_stream.wait_stream(side_stream)      # all weight gradients done before the unscale
+            unscale()
+            return
+        ei = 0
+        pending_p = None                # event of a shortcut conv still running on the side stream
+        e_in = None
+        for c in fwd_calls:
+            name = c[0].name
+            if name.endswith(".0a"):
+                e_in = ev_pool[ei]; ei += 1
+                e_in.record(main_stream)                    # block input is ready
+            if name.endswith(".0p"):
+                side_stream.wait_event(e_in)
+                c[4](ws2, stream2)
+                pending_p = ev_pool[ei]; ei += 1
+                pending_p.record(side_stream)
+                continue
+            if pending_p is not None:                       # first layer after the block: needs both branches
+                main_stream.wait_event(pending_p)
+                pending_p = None
+            c[4](ws, stream)
+        e_dy = ev_pool[ei]; ei += 1
+        e_dy.record(main_stream)                            # "the gradient the next layer consumes is ready"
+        for i in range(0, len(bwd_calls), 2):
+            cd, cw = bwd_calls[i], bwd_calls[i + 1]
+            name = cd[0].name
+            side_stream.wait_event(e_dy)
+            if name.endswith(".0p"):
+                cd[4](ws2, stream2)
+                cw[4](ws2, stream2)
+                pending_p = ev_pool[ei]; ei += 1
+                pending_p.record(side_stream)
+                continue
+            cw[4](ws2, stream2)
+            cd[4](ws, stream)
+            if name.endswith(".0a") and pending_p is not None:
+                main_stream.wait_event(pending_p)           # block-input gradient = branch + shortcut
+                pending_p = None
+            e_dy = ev_pool[ei]; ei += 1
+            e_dy.record(main_stream)
+        main_stream.wait_stream(side_stream)                # all weight gradients done before the unscale
         unscale()
-        if side_stream is not None:
-            side_stream.wait_stream(main_stream)      # the next step's gradients follow this unscale
+        side_stream.wait_stream(main_stream)                # the next step follows this unscale
 
     flops_per_step = 3 * sum(l.flops for l in layers)
 
