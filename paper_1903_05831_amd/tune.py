@@ -5,6 +5,11 @@ GPU at hand and writes the winners to csrc/tuned_table.inc (rebuild the library 
 
 The dispatcher reads SDCONV_IGEMM_VARIANT / SDCONV_WGRAD_SPLITS on every call, which is how
 this script forces a variant.  Unlisted geometries keep using the built-in heuristics.
+
+In a training step every layer finds its inputs in HBM, not in the 256 MB Infinity Cache: the
+timed calls therefore rotate over enough copies of the layer's tensors (--cold-mib of
+footprint, default 640) that no call sees data a recent call touched.  --cold-mib 0 times the
+same tensors over and over (cache-warm).
 """
 from __future__ import annotations
 
@@ -23,19 +28,23 @@ WGRAD_SPLITS = [1, 2, 3, 4, 6, 8, 12, 16, 24, 32, 48, 64, 96, 128, 192, 256]
 HERE = os.path.dirname(os.path.abspath(__file__))
 
 
-def time_call(fn, ms_budget: float) -> float:
-    for _ in range(2):
-        fn()
+def time_call(fn, ms_budget: float, ncopies: int = 1) -> float:
+    """fn(i) runs the call on copy i of the inputs; returns milliseconds per call."""
+    for i in range(2):
+        fn(i % ncopies)
     torch.cuda.synchronize()
     e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    e0.record(); fn(); e1.record(); torch.cuda.synchronize()
+    e0.record(); fn(0); e1.record(); torch.cuda.synchronize()
     t1 = max(e0.elapsed_time(e1), 1e-3)
     iters = max(3, min(500, int(ms_budget / t1)))
+    iters = max(iters, min(ncopies, 64))
     best = 1e30
+    k = 0
     for _ in range(2):
         e0.record()
         for _ in range(iters):
-            fn()
+            fn(k % ncopies)
+            k += 1
         e1.record(); torch.cuda.synchronize()
         best = min(best, e0.elapsed_time(e1) / iters)
     return best
@@ -46,6 +55,8 @@ def main() -> int:
     ap.add_argument("--configs", type=str, default="1,2,3,4,5")
     ap.add_argument("--ms", type=float, default=8.0)
     ap.add_argument("--out", type=str, default=os.path.join(HERE, "csrc", "tuned_table.inc"))
+    ap.add_argument("--cold-mib", type=int, default=640,
+                    help="rotate over copies of the inputs with this total footprint (0: one copy, cache-warm)")
     args = ap.parse_args()
     dev = torch.device("cuda:0")
     st = torch.cuda.current_stream().cuda_stream
@@ -59,9 +70,11 @@ def main() -> int:
                 continue
             seen.add(key)
             d = sd.desc_of(l)
-            x = torch.randn(l.x_shape, device=dev, dtype=torch.float16)
-            w = torch.randn(l.w_shape, device=dev, dtype=torch.float16) * 0.05
-            g = torch.randn(l.y_shape, device=dev, dtype=torch.float16)
+            foot = 2 * (l.N * l.H * l.W * l.C + l.K * l.R * l.S * l.C + l.N * l.Ho * l.Wo * l.K)
+            nc = 1 if args.cold_mib <= 0 else max(1, min(48, -(-(args.cold_mib << 20) // foot)))
+            xs = [torch.randn(l.x_shape, device=dev, dtype=torch.float16) for _ in range(nc)]
+            wts = [torch.randn(l.w_shape, device=dev, dtype=torch.float16) * 0.05 for _ in range(nc)]
+            gs = [torch.randn(l.y_shape, device=dev, dtype=torch.float16) for _ in range(nc)]
             y = torch.empty(l.y_shape, device=dev, dtype=torch.float16)
             dx = torch.empty(l.x_shape, device=dev, dtype=torch.float16)
             dw = torch.empty(l.w_shape, device=dev, dtype=torch.float32)
@@ -74,10 +87,10 @@ def main() -> int:
                         continue        # the patch kernels take stride-1 3x3-class layers only
                     ws = torch.empty(max(sd.conv2d_workspace_bytes(d, pid), 256), dtype=torch.uint8, device=dev)
                     if pid == sd.FWD:
-                        fn = lambda: sd.conv2d_fwd(d, x, w, y, ws, st)
+                        fn = lambda i: sd.conv2d_fwd(d, xs[i], wts[i], y, ws, st)
                     else:
-                        fn = lambda: sd.conv2d_dgrad(d, g, w, dx, ws, st)
-                    results.append((time_call(fn, args.ms), v))
+                        fn = lambda i: sd.conv2d_dgrad(d, gs[i], wts[i], dx, ws, st)
+                    results.append((time_call(fn, args.ms, nc), v))
                 os.environ.pop("SDCONV_IGEMM_VARIANT")
                 t, v = min(results)
                 print(f"{l.name:9s} {pname:5s} best variant {v} {t*1e3:8.1f} us {l.flops/t/1e9:7.1f} TF/s   "
@@ -93,7 +106,7 @@ def main() -> int:
                     if need > (1 << 30):
                         break
                     ws = torch.empty(max(need, 256), dtype=torch.uint8, device=dev)
-                    t = time_call(lambda: sd.conv2d_wgrad(d, x, g, dw, ws, st), args.ms)
+                    t = time_call(lambda i: sd.conv2d_wgrad(d, xs[i], gs[i], dw, ws, st), args.ms, nc)
                     results.append((t, wv, sp))
                     if t < best_t:
                         best_t, worse = t, 0
@@ -111,7 +124,7 @@ def main() -> int:
             print(f"{l.name:9s} wgrad best variant {wv} splits {sp} {t*1e3:8.1f} us {l.flops/t/1e9:7.1f} TF/s   "
                   + " ".join(f"{vv}:{tt*1e3:.0f}@{ss}" for vv, (tt, ss) in sorted(per_variant.items())), flush=True)
             lines.append(f"    {{{geom}, {sd.WGRAD}, {wv}, {sp}}},  // {l.name} wgrad {t*1e3:.1f} us")
-            del x, w, g, y, dx, dw
+            del xs, wts, gs, y, dx, dw
             torch.cuda.empty_cache()
     with open(args.out, "w") as f:
         f.write("// Written by tune.py on %s: {N,H,W,C,K,R,S,sh,sw,ph,pw,dh,dw, pass, variant, splits}\n"
