@@ -29,10 +29,15 @@ typedef _Float16 half8 __attribute__((ext_vector_type(8)));
 typedef _Float16 half4 __attribute__((ext_vector_type(4)));
 typedef float float16v __attribute__((ext_vector_type(16)));
 
-template <int BM, int BN, int WGM, int WGN, int S, int BP, bool LINEAR>
+// HF: only the upper half of the waves sends the loads (and then multiplies like the others).
+// With two waves per SIMD the lower wave keeps the matrix pipe busy while its partner is stalled
+// in the burst of LDS-DMA instructions, instead of both stalling at once (see igemm_ws.hip).
+template <int BM, int BN, int WGM, int WGN, int S, int BP, bool LINEAR, bool HF>
 __global__ __launch_bounds__(64 * WGM * WGN) void wgrad_dma_kernel(WgradParams P)
 {
-    constexpr int NW = WGM * WGN, NT = 64 * NW;
+    constexpr int NW = WGM * WGN;
+    constexpr int NWF = HF ? NW / 2 : NW, NT = 64 * NWF;    // fetching waves / threads
+    constexpr int FW0 = NW - NWF;                           // first fetching wave
     constexpr int WM = BM / WGM, WN = BN / WGN;
     constexpr int FM = WM / 32, FN = WN / 32;
     constexpr int CRG = BM / 8, CRX = BN / 8;           // 16-byte chunks per tile row
@@ -44,7 +49,7 @@ __global__ __launch_bounds__(64 * WGM * WGN) void wgrad_dma_kernel(WgradParams P
     constexpr int GMX = (BN * 2 >= 256) ? 3 : (BN * 2 / 64 - 1);
     static_assert(WM % 32 == 0 && WN % 32 == 0, "wave tile");
     static_assert(PG >= 1 && PX >= 1 && BP % RPG == 0 && BP % RPX == 0 && RPG % 4 == 0 && RPX % 4 == 0, "staging");
-    static_assert(S >= 2 && INFLIGHT < 64 && BP % 16 == 0 && BP <= NT, "pipeline");
+    static_assert(S >= 2 && INFLIGHT < 64 && BP % 16 == 0 && BP <= 64 * NW, "pipeline");
 
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
     const unsigned lds0 = (unsigned)(size_t)(__attribute__((address_space(3))) unsigned char*)smem;
@@ -53,6 +58,8 @@ __global__ __launch_bounds__(64 * WGM * WGN) void wgrad_dma_kernel(WgradParams P
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wm = wave / WGN, wn = wave % WGN;
+    const bool fetcher = wave >= FW0;
+    const int ft = tid - FW0 * 64, fw = wave - FW0;         // index among the fetching threads / waves
 
     int b = blockIdx.x;
     const int tc = b % P.tiles_c; b /= P.tiles_c;
@@ -75,14 +82,14 @@ __global__ __launch_bounds__(64 * WGM * WGN) void wgrad_dma_kernel(WgradParams P
     int x_row[PX];
 #pragma unroll
     for (int i = 0; i < PG; ++i) {
-        int row = i * RPG + tid / CRG, pc = tid % CRG;
+        int row = i * RPG + ft / CRG, pc = ft % CRG;
         int lc = ((((pc >> 2) ^ (row & GMG)) << 2) | (pc & 3));
         int k = k0 + lc * 8;
         g_off[i] = (k < P.K) ? (unsigned)((row * P.K + k) * 2) : kOutOfRange;
     }
 #pragma unroll
     for (int i = 0; i < PX; ++i) {
-        int row = i * RPX + tid / CRX, pc = tid % CRX;
+        int row = i * RPX + ft / CRX, pc = ft % CRX;
         int lc = ((((pc >> 2) ^ (row & GMX)) << 2) | (pc & 3));
         int c = c0 + lc * 8;
         x_row[i] = row;
@@ -111,7 +118,7 @@ __global__ __launch_bounds__(64 * WGM * WGN) void wgrad_dma_kernel(WgradParams P
 
     auto issue = [&](int step, int stage) {
         const int p0 = __builtin_amdgcn_readfirstlane((step0 + step) * BP);
-        const unsigned sbase = lds0 + stage * STAGE + wave * 1024;
+        const unsigned sbase = (unsigned)__builtin_amdgcn_readfirstlane((int)(lds0 + stage * STAGE + fw * 1024));
         // dy: descriptor starts at pixel p0 and ends with the tensor
         const int4v rsrcG = make_rsrc(P.G + (long)p0 * P.K, (unsigned)((P.P - p0) * P.K) * 2u);
 #pragma unroll
@@ -180,14 +187,14 @@ __global__ __launch_bounds__(64 * WGM * WGN) void wgrad_dma_kernel(WgradParams P
         int issued = 0;
 #pragma unroll
         for (int q = 0; q < S - 1; ++q)
-            if (q < nsteps) { issue(q, q); ++issued; }
+            if (q < nsteps) { if (fetcher) issue(q, q); ++issued; }
         int cs = 0, is = (S - 1) % S;
         for (int it = 0; it < nsteps; ++it) {
-            if (it + S - 2 < nsteps) wait_vmcnt<INFLIGHT>(); else wait_vmcnt<0>();
+            if (fetcher) { if (it + S - 2 < nsteps) wait_vmcnt<INFLIGHT>(); else wait_vmcnt<0>(); }
             if (!LINEAR) asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");   // table writes landed
             __builtin_amdgcn_s_barrier();
             if (issued < nsteps) {
-                issue(issued, is);
+                if (fetcher) issue(issued, is);
                 ++issued;
                 is = (is + 1 == S) ? 0 : is + 1;
             }
@@ -217,7 +224,7 @@ __global__ __launch_bounds__(64 * WGM * WGN) void wgrad_dma_kernel(WgradParams P
         }
 }
 
-template <int BM, int BN, int WGM, int WGN, int S, int BP>
+template <int BM, int BN, int WGM, int WGN, int S, int BP, bool HF = false>
 static hipError_t launch_wdma(const WgradParams& P, hipStream_t st)
 {
     constexpr size_t lds = (size_t)S * BP * (BM + BN) * 2 + (size_t)S * BP * sizeof(unsigned);
@@ -226,21 +233,21 @@ static hipError_t launch_wdma(const WgradParams& P, hipStream_t st)
     static bool configured = false;
     if (!configured) {
         hipError_t e = hipFuncSetAttribute(
-            reinterpret_cast<const void*>(&wgrad_dma_kernel<BM, BN, WGM, WGN, S, BP, false>),
+            reinterpret_cast<const void*>(&wgrad_dma_kernel<BM, BN, WGM, WGN, S, BP, false, HF>),
             hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         if (e != hipSuccess) return e;
         e = hipFuncSetAttribute(
-            reinterpret_cast<const void*>(&wgrad_dma_kernel<BM, BN, WGM, WGN, S, BP, true>),
+            reinterpret_cast<const void*>(&wgrad_dma_kernel<BM, BN, WGM, WGN, S, BP, true, HF>),
             hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         if (e != hipSuccess) return e;
         configured = true;
     }
     long blocks = (long)P.tiles_c * P.tiles_k * P.R * P.S * P.splits;
     if (linear)
-        hipLaunchKernelGGL((wgrad_dma_kernel<BM, BN, WGM, WGN, S, BP, true>), dim3((unsigned)blocks),
+        hipLaunchKernelGGL((wgrad_dma_kernel<BM, BN, WGM, WGN, S, BP, true, HF>), dim3((unsigned)blocks),
                            dim3(64 * WGM * WGN), lds, st, P);
     else
-        hipLaunchKernelGGL((wgrad_dma_kernel<BM, BN, WGM, WGN, S, BP, false>), dim3((unsigned)blocks),
+        hipLaunchKernelGGL((wgrad_dma_kernel<BM, BN, WGM, WGN, S, BP, false, HF>), dim3((unsigned)blocks),
                            dim3(64 * WGM * WGN), lds, st, P);
     return hipGetLastError();
 }
@@ -255,6 +262,11 @@ const WgradVariant kWgradDmaVariants[kNumWgradDmaVariants] = {
     {64, 256, "wgrad_dma_64x256x64_4w_s2"},
     {64, 64, "wgrad_dma_64x64x64_4w_s3"},
     {128, 64, "wgrad_dma_128x64x64_4w_s3"},
+    {256, 256, "wgrad_dma_256x256x64_8w_s2_hf"},
+    {256, 256, "wgrad_dma_256x256x32_8w_s3_hf"},
+    {256, 128, "wgrad_dma_256x128x32_8w_s3_hf"},
+    {128, 128, "wgrad_dma_128x128x64_8w_s3_hf"},
+    {256, 128, "wgrad_dma_256x128x64_8w_s3_hf"},
 };
 
 hipError_t launch_wgrad_dma(int variant, const WgradParams& P, hipStream_t st)
@@ -269,6 +281,11 @@ hipError_t launch_wgrad_dma(int variant, const WgradParams& P, hipStream_t st)
         case 6: return launch_wdma<64, 256, 1, 4, 2, 64>(P, st);
         case 7: return launch_wdma<64, 64, 2, 2, 3, 64>(P, st);
         case 8: return launch_wdma<128, 64, 2, 2, 3, 64>(P, st);
+        case 9: return launch_wdma<256, 256, 2, 4, 2, 64, true>(P, st);
+        case 10: return launch_wdma<256, 256, 2, 4, 3, 32, true>(P, st);
+        case 11: return launch_wdma<256, 128, 4, 2, 3, 32, true>(P, st);
+        case 12: return launch_wdma<128, 128, 2, 4, 3, 64, true>(P, st);
+        case 13: return launch_wdma<256, 128, 4, 2, 3, 64, true>(P, st);
         default: return hipErrorInvalidValue;
     }
 }

@@ -81,3 +81,21 @@ def test_split_role_kernel_variants(variant):
         with forced(SDCONV_IGEMM_VARIANT=variant, SDCONV_NO_TUNED_TABLE=1):
             assert "_ws_" in sd.kernel_name(d, sd.FWD)
             check_all_passes(d, x, w, g, f"ws{variant}{case}")
+
+
+WGRAD_SHAPES = [
+    (2, 23, 29, 64, 72, 3, 3, (2, 2), (1, 1), (1, 1)),      # strided, gathered x rows, filter tail
+    (1, 31, 37, 136, 200, 3, 3, (1, 1), (1, 1), (1, 1)),    # channel and filter tails
+    (1, 31, 37, 128, 264, 1, 1, (1, 1), (0, 0), (1, 1)),    # 1x1 unpadded: linear x addressing
+]
+WGRAD_VARIANTS = list(range(100, 114))
+
+
+@pytest.mark.parametrize("variant", WGRAD_VARIANTS)
+def test_wgrad_kernel_variants(variant):
+    for splits in (1, 3):
+        for case in WGRAD_SHAPES:
+            say(f"wgrad variant {variant} splits {splits} case {case}")
+            d, x, w, g = _rand_case(*case, seed=variant * 13 + splits)
+            with forced(SDCONV_WGRAD_VARIANT=variant, SDCONV_WGRAD_SPLITS=splits, SDCONV_NO_TUNED_TABLE=1):
+                check_all_passes(d, x, w, g, f"wgrad{variant}s{splits}{case}")
