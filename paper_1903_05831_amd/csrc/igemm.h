@@ -36,7 +36,7 @@ hipError_t launch_igemm_dma(int variant, const IgemmParams& P, hipStream_t st);
 constexpr int kNumIgemmPersVariants = 10;
 extern const IgemmVariant kIgemmPersVariants[kNumIgemmPersVariants];
 hipError_t launch_igemm_pers(int variant, const IgemmParams& P, hipStream_t st);
-constexpr int kNumIgemmWsVariants = 10;
+constexpr int kNumIgemmWsVariants = 17;
 extern const IgemmVariant kIgemmWsVariants[kNumIgemmWsVariants];
 hipError_t launch_igemm_ws(int variant, const IgemmParams& P, hipStream_t st);
 struct PatchVariant { int th, tw, bn; const char* fwd_name; const char* dgrad_name; };

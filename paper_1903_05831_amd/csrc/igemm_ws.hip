@@ -20,6 +20,7 @@
 // Row addressing is computed once per workgroup by all threads (one tile row each: byte offset
 // of the pixel at tap displacement 0 and a bit mask of the taps inside the image) and handed to
 // the fetching waves through LDS.
+#include <type_traits>
 #include "common.h"
 #include "igemm.h"
 #include "dma.h"
@@ -31,8 +32,12 @@ namespace sdconv {
 typedef _Float16 half8 __attribute__((ext_vector_type(8)));
 typedef _Float16 half4 __attribute__((ext_vector_type(4)));
 typedef float float16v __attribute__((ext_vector_type(16)));
+typedef float float4v_ __attribute__((ext_vector_type(4)));
 
-template <int MODE, int BM, int BN, int WGM, int WGN, int S, int BK, int NP>
+// MF: 32 = v_mfma_f32_32x32x16_f16 blocks; 16 = v_mfma_f32_16x16x32_f16 blocks, for tile heights
+// that are a multiple of 16 but not of 32 per wave row (224 = 2 x 112 rows: 25088 = 112 x 224
+// pixels of the RoI head then give 224 or 896 tiles instead of 196 or 784 for 256 CUs).
+template <int MODE, int BM, int BN, int WGM, int WGN, int S, int BK, int NP, int MF = 32>
 __global__ __launch_bounds__(64 * (WGM * WGN + NP)) void igemm_ws_kernel(IgemmParams P)
 {
     constexpr int NWC = WGM * WGN;                  // multiplying waves
@@ -40,7 +45,8 @@ __global__ __launch_bounds__(64 * (WGM * WGN + NP)) void igemm_ws_kernel(IgemmPa
     constexpr int NI = NP ? NP : NWC / 2;           // fetching waves
     constexpr int IW0 = NP ? NWC : NWC / 2;         // first fetching wave
     constexpr int WM = BM / WGM, WN = BN / WGN;
-    constexpr int FM = WM / 32, FN = WN / 32;
+    constexpr int FM = WM / MF, FN = WN / MF;
+    constexpr int ACCN = MF == 32 ? 16 : 4;         // accumulator floats per lane and block
     constexpr int CPR = BK / 8;                     // 16-byte chunks per tile row
     constexpr int ROWB = BK * 2;                    // bytes per tile row
     constexpr int SWS = (CPR == 8) ? 1 : 2;         // swizzle: chunk ^= (row >> SWS) & (CPR-1)
@@ -48,7 +54,8 @@ __global__ __launch_bounds__(64 * (WGM * WGN + NP)) void igemm_ws_kernel(IgemmPa
     constexpr int PA = BM / RPP, PB = BN / RPP;     // loads per fetching thread and stage
     constexpr int STAGE = (BM + BN) * ROWB;         // bytes
     constexpr int INFLIGHT = (S - 2) * (PA + PB);   // loads a fetching wave may leave outstanding
-    static_assert(WM % 32 == 0 && WN % 32 == 0 && BM % RPP == 0 && BN % RPP == 0, "tile shape");
+    static_assert((MF == 32 || MF == 16) && WM % MF == 0 && WN % MF == 0 && BM % RPP == 0 && BN % RPP == 0, "tile shape");
+    static_assert(MF == 32 || BK == 64, "16x16x32 blocks take 32 contraction values per instruction");
     static_assert(S >= 2 && INFLIGHT < 64, "pipeline depth");
     static_assert(BK == 64 || BK == 32, "contraction step");
     static_assert(MODE == 0 || (BK == 64 && (64 * NI) % (BN / 8) == 0), "data-gradient filter tile");
@@ -235,41 +242,51 @@ __global__ __launch_bounds__(64 * (WGM * WGN + NP)) void igemm_ws_kernel(IgemmPa
 
     // ---- multiplying side ------------------------------------------------------------------
     const int wm = wave / WGN, wn = wave % WGN;
-    float16v acc[FN][FM];
+    typedef typename std::conditional<MF == 32, float16v, float4v_>::type acc_t;
+    acc_t acc[FN][FM];
 #pragma unroll
     for (int a = 0; a < FN; ++a)
 #pragma unroll
         for (int b = 0; b < FM; ++b)
 #pragma unroll
-            for (int e = 0; e < 16; ++e) acc[a][b][e] = 0.f;
+            for (int e = 0; e < ACCN; ++e) acc[a][b][e] = 0.f;
 
-    const int l32 = lane & 31, lhi = lane >> 5;
+    // fragment lane mapping: row (or column) lane % MF of a block, contraction chunk lane / MF
+    const int frow = lane & (MF - 1), lhi = lane / MF;
+    constexpr int KSTEP = MF == 32 ? 16 : 32;       // contraction values per MFMA
+    constexpr int CPK = KSTEP / 8;                  // 16-byte chunks per MFMA step
     auto compute = [&](int stage) {
         const unsigned char* sa = smem + stage * STAGE;
         const unsigned char* sb = sa + BM * ROWB;
 #pragma unroll
-        for (int kk = 0; kk < BK / 16; ++kk) {
-            const int chunk = kk * 2 + lhi;
+        for (int kk = 0; kk < BK / KSTEP; ++kk) {
+            const int chunk = kk * CPK + lhi;
             half8 fa[FM], fb[FN];
 #pragma unroll
             for (int b = 0; b < FM; ++b) {
-                int row = wm * WM + b * 32 + l32;
+                int row = wm * WM + b * MF + frow;
                 fa[b] = *reinterpret_cast<const half8*>(sa + row * ROWB + ((chunk ^ ((row >> SWS) & (CPR - 1))) << 4));
             }
 #pragma unroll
             for (int a = 0; a < FN; ++a) {
                 if (MODE == 0) {
-                    int row = wn * WN + a * 32 + l32;
+                    int row = wn * WN + a * MF + frow;
                     fb[a] = *reinterpret_cast<const half8*>(sb + row * ROWB + ((chunk ^ ((row >> SWS) & (CPR - 1))) << 4));
-                } else {
+                } else if (MF == 32) {
                     fb[a] = lds_frag_tr<BN>(sb, kk * 16, wn * WN + a * 32, lane);
+                } else {
+                    fb[a] = lds_frag_tr_16<BN>(sb, kk * 32, wn * WN + a * 16, lane);
                 }
             }
 #pragma unroll
             for (int a = 0; a < FN; ++a)
 #pragma unroll
-                for (int b = 0; b < FM; ++b)
-                    acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_f16(fb[a], fa[b], acc[a][b], 0, 0, 0);
+                for (int b = 0; b < FM; ++b) {
+                    if constexpr (MF == 32)
+                        acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_f16(fb[a], fa[b], acc[a][b], 0, 0, 0);
+                    else
+                        acc[a][b] = __builtin_amdgcn_mfma_f32_16x16x32_f16(fb[a], fa[b], acc[a][b], 0, 0, 0);
+                }
         }
     };
 
@@ -299,13 +316,13 @@ __global__ __launch_bounds__(64 * (WGM * WGN + NP)) void igemm_ws_kernel(IgemmPa
     }
 
     // ---- epilogue: through a per-wave LDS strip into 16-byte NHWC stores --------------------
-    static_assert(NWC * epilogue_strip_bytes<WN>() <= S * STAGE, "epilogue strips fit in the ring");
+    static_assert(NWC * epilogue_strip_bytes<WN, MF>() <= S * STAGE, "epilogue strips fit in the ring");
     __builtin_amdgcn_s_barrier();                   // everybody is done reading the last stage
-    store_tile_via_lds<FM, FN>(acc, smem + wave * epilogue_strip_bytes<WN>(), lane, m0 + wm * WM, n0 + wn * WN,
+    store_tile_via_lds<FM, FN, MF>(acc, smem + wave * epilogue_strip_bytes<WN, MF>(), lane, m0 + wm * WM, n0 + wn * WN,
                                Mcls, P, Hi, Wj, eh, ew, ca, cb);
 }
 
-template <int MODE, int BM, int BN, int WGM, int WGN, int S, int BK, int NP>
+template <int MODE, int BM, int BN, int WGM, int WGN, int S, int BK, int NP, int MF = 32>
 static hipError_t launch_ws_variant(const IgemmParams& P, hipStream_t st)
 {
     constexpr size_t lds = (size_t)S * (BM + BN) * BK * 2 + (4 * kMaxTaps + 4) * sizeof(int) + (size_t)BM * 12;
@@ -313,13 +330,13 @@ static hipError_t launch_ws_variant(const IgemmParams& P, hipStream_t st)
     static bool configured = false;
     if (!configured) {
         hipError_t e = hipFuncSetAttribute(
-            reinterpret_cast<const void*>(&igemm_ws_kernel<MODE, BM, BN, WGM, WGN, S, BK, NP>),
+            reinterpret_cast<const void*>(&igemm_ws_kernel<MODE, BM, BN, WGM, WGN, S, BK, NP, MF>),
             hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         if (e != hipSuccess) return e;
         configured = true;
     }
     const int grid = ((P.total_tiles + 63) / 64) * 64;   // whole runs of 8 tiles on each of 8 XCDs
-    hipLaunchKernelGGL((igemm_ws_kernel<MODE, BM, BN, WGM, WGN, S, BK, NP>), dim3(grid),
+    hipLaunchKernelGGL((igemm_ws_kernel<MODE, BM, BN, WGM, WGN, S, BK, NP, MF>), dim3(grid),
                        dim3(64 * (WGM * WGN + NP)), lds, st, P);
     return hipGetLastError();
 }
@@ -335,6 +352,13 @@ const IgemmVariant kIgemmWsVariants[kNumIgemmWsVariants] = {
     {128, 64, "igemm_fwd_ws_128x64x64_4w2f_s4", "igemm_dgrad_ws_128x64x64_4w2f_s4"},
     {128, 64, "igemm_fwd_ws_128x64x64_8w0f_s4", "igemm_dgrad_ws_128x64x64_8w0f_s4"},
     {128, 256, "igemm_fwd_ws_128x256x64_8w0f_s3", "igemm_dgrad_ws_128x256x64_8w0f_s3"},
+    {224, 256, "igemm_fwd_ws_224x256x64_8w0f_s2_m16", "igemm_dgrad_ws_224x256x64_8w0f_s2_m16"},
+    {256, 256, "igemm_fwd_ws_256x256x64_8w0f_s2_m16", "igemm_dgrad_ws_256x256x64_8w0f_s2_m16"},
+    {128, 128, "igemm_fwd_ws_128x128x64_4w2f_s3_m16", "igemm_dgrad_ws_128x128x64_4w2f_s3_m16"},
+    {256, 128, "igemm_fwd_ws_256x128x64_8w2f_s3_m16", "igemm_dgrad_ws_256x128x64_8w2f_s3_m16"},
+    {256, 128, "igemm_fwd_ws_256x128x64_8w0f_s3_m16", "igemm_dgrad_ws_256x128x64_8w0f_s3_m16"},
+    {128, 256, "igemm_fwd_ws_128x256x64_8w0f_s3_m16", "igemm_dgrad_ws_128x256x64_8w0f_s3_m16"},
+    {224, 128, "igemm_fwd_ws_224x128x64_8w0f_s3_m16", "igemm_dgrad_ws_224x128x64_8w0f_s3_m16"},
 };
 
 #define SDCONV_WS_CASE(idx, BM, BN, WGM, WGN, S, BK, NP)                                      \
@@ -355,6 +379,20 @@ hipError_t launch_igemm_ws(int variant, const IgemmParams& P, hipStream_t st)
         SDCONV_WS_CASE(7, 128, 64, 2, 2, 4, 64, 2)
         SDCONV_WS_CASE(8, 128, 64, 4, 2, 4, 64, 0)
         SDCONV_WS_CASE(9, 128, 256, 2, 4, 3, 64, 0)
+        case 20: return launch_ws_variant<0, 224, 256, 2, 4, 2, 64, 0, 16>(P, st);
+        case 21: return launch_ws_variant<1, 224, 256, 2, 4, 2, 64, 0, 16>(P, st);
+        case 22: return launch_ws_variant<0, 256, 256, 2, 4, 2, 64, 0, 16>(P, st);
+        case 23: return launch_ws_variant<1, 256, 256, 2, 4, 2, 64, 0, 16>(P, st);
+        case 24: return launch_ws_variant<0, 128, 128, 2, 2, 3, 64, 2, 16>(P, st);
+        case 25: return launch_ws_variant<1, 128, 128, 2, 2, 3, 64, 2, 16>(P, st);
+        case 26: return launch_ws_variant<0, 256, 128, 4, 2, 3, 64, 2, 16>(P, st);
+        case 27: return launch_ws_variant<1, 256, 128, 4, 2, 3, 64, 2, 16>(P, st);
+        case 28: return launch_ws_variant<0, 256, 128, 4, 2, 3, 64, 0, 16>(P, st);
+        case 29: return launch_ws_variant<1, 256, 128, 4, 2, 3, 64, 0, 16>(P, st);
+        case 30: return launch_ws_variant<0, 128, 256, 2, 4, 3, 64, 0, 16>(P, st);
+        case 31: return launch_ws_variant<1, 128, 256, 2, 4, 3, 64, 0, 16>(P, st);
+        case 32: return launch_ws_variant<0, 224, 128, 2, 4, 3, 64, 0, 16>(P, st);
+        case 33: return launch_ws_variant<1, 224, 128, 2, 4, 3, 64, 0, 16>(P, st);
         default: return hipErrorInvalidValue;
     }
 }

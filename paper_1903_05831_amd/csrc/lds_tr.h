@@ -59,4 +59,17 @@ __device__ __forceinline__ tr_half8 lds_frag_tr(const unsigned char* tile, int r
     return __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
 }
 
+// Same for v_mfma_f32_16x16x32_f16: fragment of the 16 columns starting at col0 (a multiple of
+// 16), contraction rows row0 .. row0+31 (lane group g = lane/16 gets rows +8g..8g+7).
+template <int BW>
+__device__ __forceinline__ tr_half8 lds_frag_tr_16(const unsigned char* tile, int row0, int col0, int lane)
+{
+    const int grp = lane >> 4, gl = lane & 15;
+    const int row = row0 + 8 * grp + (gl >> 2);
+    const int col = col0 + 4 * (gl & 3);
+    tr_half4 lo = lds_read_tr16(tile + sw_off<BW>(row, col));
+    tr_half4 hi = lds_read_tr16(tile + sw_off<BW>(row + 4, col));
+    return __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+}
+
 }  // namespace sdconv

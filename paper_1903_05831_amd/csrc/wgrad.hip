@@ -193,19 +193,37 @@ __global__ __launch_bounds__(kWThreads) void wgrad_kernel(WgradParams P)
         }
 }
 
-// dw[e] = partial[0][e] + partial[1][e] + ... in that order.
+// dw[e] = sum over the splits of partial[k][e], in a fixed order: G groups of threads take the
+// splits k = g, g+G, g+2G, ... of an element each (in that order), then group 0 adds the G
+// group sums in group order.  G > 1 keeps small gradients with many splits from running on a
+// handful of threads with a long serial chain of loads each; any G gives run-to-run identical
+// results for a given (numel, splits), since G is a function of those two only.
 __global__ __launch_bounds__(256) void splitk_reduce_kernel(const float* __restrict__ partial,
-                                                            float* __restrict__ dw, int splits, long numel4)
+                                                            float* __restrict__ dw, int splits, long numel4, int G)
 {
-    long i = (long)blockIdx.x * 256 + threadIdx.x;
-    if (i >= numel4) return;
+    __shared__ float4v sh[256];
+    const int epb = 256 / G;                        // elements (of 4 floats) per block
+    const int e = threadIdx.x % epb, g = threadIdx.x / epb;
+    const long i = (long)blockIdx.x * epb + e;
     const float4v* p = reinterpret_cast<const float4v*>(partial);
-    float4v s = p[i];
-    for (int k = 1; k < splits; ++k) {
-        float4v v = p[(long)k * numel4 + i];
-        s.x += v.x; s.y += v.y; s.z += v.z; s.w += v.w;
+    float4v s = {0.f, 0.f, 0.f, 0.f};
+    if (i < numel4) {
+        for (int k = g; k < splits; k += G) {
+            float4v v = p[(long)k * numel4 + i];
+            s.x += v.x; s.y += v.y; s.z += v.z; s.w += v.w;
+        }
     }
-    reinterpret_cast<float4v*>(dw)[i] = s;
+    if (G > 1) {
+        sh[threadIdx.x] = s;
+        __syncthreads();
+        if (g == 0) {
+            for (int gg = 1; gg < G; ++gg) {
+                float4v v = sh[gg * epb + e];
+                s.x += v.x; s.y += v.y; s.z += v.z; s.w += v.w;
+            }
+        }
+    }
+    if (g == 0 && i < numel4) reinterpret_cast<float4v*>(dw)[i] = s;
 }
 
 template <int BM, int BN, int WGM, int WGN>
@@ -241,8 +259,11 @@ hipError_t launch_wgrad(int variant, const WgradParams& P, hipStream_t st)
 hipError_t launch_splitk_reduce(const float* partial, float* dw, int splits, long numel, hipStream_t st)
 {
     long n4 = numel / 4;   // numel is a multiple of 64 on this route (C and K multiples of 8)
-    hipLaunchKernelGGL(splitk_reduce_kernel, dim3((unsigned)((n4 + 255) / 256)), dim3(256), 0, st,
-                       partial, dw, splits, n4);
+    int G = 1;
+    while (G < 16 && G * 2 <= splits && n4 * G < 65536) G *= 2;
+    const int epb = 256 / G;
+    hipLaunchKernelGGL(splitk_reduce_kernel, dim3((unsigned)((n4 + epb - 1) / epb)), dim3(256), 0, st,
+                       partial, dw, splits, n4, G);
     return hipGetLastError();
 }
 

@@ -22,7 +22,7 @@ import torch
 import paper_1903_05831_amd as sd
 from paper_1903_05831_amd import workloads
 
-FWD_DGRAD_VARIANTS = [100, 101, 105, 106, 107, 108, 300, 302, 303, 306, 309, 400, 401, 403, 404]
+FWD_DGRAD_VARIANTS = [100, 101, 105, 106, 107, 108, 300, 302, 303, 306, 309, 310, 311, 312, 313, 314, 315, 316, 400, 401, 403, 404]
 WGRAD_VARIANTS = [100, 101, 102, 104, 105, 107, 108, 109, 110, 111, 112, 113]
 WGRAD_SPLITS = [1, 2, 3, 4, 6, 8, 12, 16, 24, 32, 48, 64, 96, 128, 192, 256]
 HERE = os.path.dirname(os.path.abspath(__file__))
