@@ -18,6 +18,7 @@
 // source channels a multiple of 64.  The data gradient of such a layer is the same kind of
 // convolution over dy with displaced taps; it reads the filter as stored, [K][R][S][C], as
 // 64-filter x BN-channel tiles that the transposing LDS read turns into fragments (lds_tr.h).
+#include <type_traits>
 #include "common.h"
 #include "igemm.h"
 #include "dma.h"
@@ -28,21 +29,24 @@ namespace sdconv {
 
 typedef _Float16 half8 __attribute__((ext_vector_type(8)));
 typedef float float16v __attribute__((ext_vector_type(16)));
+typedef float float4p __attribute__((ext_vector_type(4)));
 
-template <int MODE, int TH, int TW, int BN, int WGM, int WGN, int SB>
+// MF: 32 = v_mfma_f32_32x32x16_f16 blocks, 16 = v_mfma_f32_16x16x32_f16 blocks.
+template <int MODE, int TH, int TW, int BN, int WGM, int WGN, int SB, int MF = 32>
 __global__ __launch_bounds__(64 * WGM * WGN) void conv_patch_kernel(IgemmParams P)
 {
     constexpr int EH = 2, EW = 2;                   // extra patch rows / columns
     constexpr int PH = TH + EH, PW = TW + EW, PPX = PH * PW;
     constexpr int NW = WGM * WGN, NI = NW / 2, IW0 = NW / 2;
     constexpr int BM = TH * TW, WM = BM / WGM, WN = BN / WGN;
-    constexpr int FM = WM / 32, FN = WN / 32;
+    constexpr int FM = WM / MF, FN = WN / MF;
+    constexpr int ACCN = MF == 32 ? 16 : 4, KSTEP = MF == 32 ? 16 : 32, CPK = KSTEP / 8;
     constexpr int NPL = (PPX + 8 * NI - 1) / (8 * NI);     // patch loads per fetching lane
     constexpr int PATCHB = NPL * NI * 1024;                // bytes of one patch buffer
     constexpr int PB = BN / (8 * NI);                      // filter loads per fetching lane and tap
     constexpr int BSTAGE = BN * 128;
     constexpr int D = SB - 1;                              // filter stages in flight
-    static_assert(NW % 2 == 0 && WM % 32 == 0 && WN % 32 == 0 && BN % (8 * NI) == 0, "tile shape");
+    static_assert((MF == 32 || MF == 16) && NW % 2 == 0 && WM % MF == 0 && WN % MF == 0 && BN % (8 * NI) == 0, "tile shape");
     static_assert(SB >= 2 && NPL + D * PB < 64, "loads in flight");   // vmcnt is a 6-bit counter
 
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
@@ -139,20 +143,21 @@ __global__ __launch_bounds__(64 * WGM * WGN) void conv_patch_kernel(IgemmParams 
 
     // ---- multiplying side ------------------------------------------------------------------
     const int wm = wave / WGN, wn = wave % WGN;
-    const int l32 = lane & 31, lhi = lane >> 5;
+    const int frow = lane & (MF - 1), lhi = lane / MF;
     int pbase[FM];                                  // patch pixel of this lane's row at displacement 0
 #pragma unroll
     for (int b = 0; b < FM; ++b) {
-        const int ml = wm * WM + b * 32 + l32;
+        const int ml = wm * WM + b * MF + frow;
         pbase[b] = (ml / TW) * PW + (ml % TW);
     }
-    float16v acc[FN][FM];
+    typedef typename std::conditional<MF == 32, float16v, float4p>::type acc_t;
+    acc_t acc[FN][FM];
 #pragma unroll
     for (int a = 0; a < FN; ++a)
 #pragma unroll
         for (int b = 0; b < FM; ++b)
 #pragma unroll
-            for (int e = 0; e < 16; ++e) acc[a][b][e] = 0.f;
+            for (int e = 0; e < ACCN; ++e) acc[a][b][e] = 0.f;
 
     auto compute = [&](int kc, int tap, int stage) {
         const unsigned char* pa = smem + (kc & 1) * PATCHB;
@@ -162,8 +167,8 @@ __global__ __launch_bounds__(64 * WGM * WGN) void conv_patch_kernel(IgemmParams 
 #pragma unroll
         for (int b = 0; b < FM; ++b) prow[b] = pbase[b] + po;
 #pragma unroll
-        for (int kk = 0; kk < 4; ++kk) {
-            const int chunk = kk * 2 + lhi;
+        for (int kk = 0; kk < 64 / KSTEP; ++kk) {
+            const int chunk = kk * CPK + lhi;
             half8 fa[FM], fb[FN];
 #pragma unroll
             for (int b = 0; b < FM; ++b)
@@ -171,17 +176,23 @@ __global__ __launch_bounds__(64 * WGM * WGN) void conv_patch_kernel(IgemmParams 
 #pragma unroll
             for (int a = 0; a < FN; ++a) {
                 if (MODE == 0) {
-                    const int row = wn * WN + a * 32 + l32;
+                    const int row = wn * WN + a * MF + frow;
                     fb[a] = *reinterpret_cast<const half8*>(sb + row * 128 + ((chunk ^ ((row >> 1) & 7)) << 4));
-                } else {
+                } else if (MF == 32) {
                     fb[a] = lds_frag_tr<BN>(sb, kk * 16, wn * WN + a * 32, lane);
+                } else {
+                    fb[a] = lds_frag_tr_16<BN>(sb, kk * 32, wn * WN + a * 16, lane);
                 }
             }
 #pragma unroll
             for (int a = 0; a < FN; ++a)
 #pragma unroll
-                for (int b = 0; b < FM; ++b)
-                    acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_f16(fb[a], fa[b], acc[a][b], 0, 0, 0);
+                for (int b = 0; b < FM; ++b) {
+                    if constexpr (MF == 32)
+                        acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_f16(fb[a], fa[b], acc[a][b], 0, 0, 0);
+                    else
+                        acc[a][b] = __builtin_amdgcn_mfma_f32_16x16x32_f16(fb[a], fa[b], acc[a][b], 0, 0, 0);
+                }
         }
     };
 
@@ -215,9 +226,9 @@ __global__ __launch_bounds__(64 * WGM * WGN) void conv_patch_kernel(IgemmParams 
     }
 
     // ---- epilogue ------------------------------------------------------------------------------
-    static_assert(NW * epilogue_strip_bytes<WN>() <= 2 * PATCHB, "epilogue strips fit in the patch buffers");
+    static_assert(NW * epilogue_strip_bytes<WN, MF>() <= 2 * PATCHB, "epilogue strips fit in the patch buffers");
     __builtin_amdgcn_s_barrier();                   // everybody is done reading the last patch
-    store_rows_via_lds<FM, FN>(acc, smem + wave * epilogue_strip_bytes<WN>(), lane, n0 + wn * WN, P,
+    store_rows_via_lds<FM, FN, MF>(acc, smem + wave * epilogue_strip_bytes<WN, MF>(), lane, n0 + wn * WN, P,
                                [&](int r) -> long {
         const int ml = wm * WM + r;
         const int h = h0 + ml / TW, w = w0 + ml % TW;
@@ -226,7 +237,7 @@ __global__ __launch_bounds__(64 * WGM * WGN) void conv_patch_kernel(IgemmParams 
     });
 }
 
-template <int MODE, int TH, int TW, int BN, int WGM, int WGN, int SB>
+template <int MODE, int TH, int TW, int BN, int WGM, int WGN, int SB, int MF = 32>
 static hipError_t launch_patch_variant(const IgemmParams& P, hipStream_t st)
 {
     constexpr int NI = WGM * WGN / 2;
@@ -236,13 +247,13 @@ static hipError_t launch_patch_variant(const IgemmParams& P, hipStream_t st)
     static bool configured = false;
     if (!configured) {
         hipError_t e = hipFuncSetAttribute(
-            reinterpret_cast<const void*>(&conv_patch_kernel<MODE, TH, TW, BN, WGM, WGN, SB>),
+            reinterpret_cast<const void*>(&conv_patch_kernel<MODE, TH, TW, BN, WGM, WGN, SB, MF>),
             hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         if (e != hipSuccess) return e;
         configured = true;
     }
     const int grid = ((P.total_tiles + 63) / 64) * 64;
-    hipLaunchKernelGGL((conv_patch_kernel<MODE, TH, TW, BN, WGM, WGN, SB>), dim3(grid), dim3(64 * WGM * WGN),
+    hipLaunchKernelGGL((conv_patch_kernel<MODE, TH, TW, BN, WGM, WGN, SB, MF>), dim3(grid), dim3(64 * WGM * WGN),
                        lds, st, P);
     return hipGetLastError();
 }
@@ -254,6 +265,12 @@ const PatchVariant kPatchVariants[kNumPatchVariants] = {
     {16, 16, 64, "conv_fwd_patch_16x16x64_s4", "conv_dgrad_patch_16x16x64_s4"},
     {8, 32, 128, "conv_fwd_patch_8x32x128_s3", "conv_dgrad_patch_8x32x128_s3"},
     {8, 16, 64, "conv_fwd_patch_8x16x64_s4", "conv_dgrad_patch_8x16x64_s4"},
+    {16, 16, 128, "conv_fwd_patch_16x16x128_s3_m16", "conv_dgrad_patch_16x16x128_s3_m16"},
+    {8, 16, 128, "conv_fwd_patch_8x16x128_s4_m16", "conv_dgrad_patch_8x16x128_s4_m16"},
+    {16, 16, 64, "conv_fwd_patch_16x16x64_s4_m16", "conv_dgrad_patch_16x16x64_s4_m16"},
+    {8, 32, 128, "conv_fwd_patch_8x32x128_s3_m16", "conv_dgrad_patch_8x32x128_s3_m16"},
+    {7, 16, 128, "conv_fwd_patch_7x16x128_s4_m16", "conv_dgrad_patch_7x16x128_s4_m16"},
+    {7, 16, 256, "conv_fwd_patch_7x16x256_s3_m16", "conv_dgrad_patch_7x16x256_s3_m16"},
 };
 
 #define SDCONV_PATCH_CASE(idx, TH, TW, BN, WGM, WGN, SB)                                      \
@@ -270,6 +287,18 @@ hipError_t launch_conv_patch(int variant, const IgemmParams& P, hipStream_t st)
         SDCONV_PATCH_CASE(3, 16, 16, 64, 4, 2, 4)
         SDCONV_PATCH_CASE(4, 8, 32, 128, 4, 2, 3)
         SDCONV_PATCH_CASE(5, 8, 16, 64, 4, 2, 4)
+        case 12: return launch_patch_variant<0, 16, 16, 128, 4, 2, 3, 16>(P, st);
+        case 13: return launch_patch_variant<1, 16, 16, 128, 4, 2, 3, 16>(P, st);
+        case 14: return launch_patch_variant<0, 8, 16, 128, 2, 4, 4, 16>(P, st);
+        case 15: return launch_patch_variant<1, 8, 16, 128, 2, 4, 4, 16>(P, st);
+        case 16: return launch_patch_variant<0, 16, 16, 64, 4, 2, 4, 16>(P, st);
+        case 17: return launch_patch_variant<1, 16, 16, 64, 4, 2, 4, 16>(P, st);
+        case 18: return launch_patch_variant<0, 8, 32, 128, 4, 2, 3, 16>(P, st);
+        case 19: return launch_patch_variant<1, 8, 32, 128, 4, 2, 3, 16>(P, st);
+        case 20: return launch_patch_variant<0, 7, 16, 128, 1, 8, 4, 16>(P, st);
+        case 21: return launch_patch_variant<1, 7, 16, 128, 1, 8, 4, 16>(P, st);
+        case 22: return launch_patch_variant<0, 7, 16, 256, 1, 8, 3, 16>(P, st);
+        case 23: return launch_patch_variant<1, 7, 16, 256, 1, 8, 3, 16>(P, st);
         default: return hipErrorInvalidValue;
     }
 }

@@ -40,7 +40,7 @@ constexpr int kNumIgemmWsVariants = 17;
 extern const IgemmVariant kIgemmWsVariants[kNumIgemmWsVariants];
 hipError_t launch_igemm_ws(int variant, const IgemmParams& P, hipStream_t st);
 struct PatchVariant { int th, tw, bn; const char* fwd_name; const char* dgrad_name; };
-constexpr int kNumPatchVariants = 6;
+constexpr int kNumPatchVariants = 12;
 extern const PatchVariant kPatchVariants[kNumPatchVariants];
 hipError_t launch_conv_patch(int variant, const IgemmParams& P, hipStream_t st);
 hipError_t launch_igemm(int variant, const IgemmParams& P, int total_tiles, hipStream_t st);

@@ -21,7 +21,7 @@ struct WgradVariant { int bm, bn; const char* name; };
 constexpr int kNumWgradVariants = 2;
 extern const WgradVariant kWgradVariants[kNumWgradVariants];
 
-constexpr int kNumWgradDmaVariants = 14;
+constexpr int kNumWgradDmaVariants = 21;
 extern const WgradVariant kWgradDmaVariants[kNumWgradDmaVariants];
 hipError_t launch_wgrad_dma(int variant, const WgradParams& P, hipStream_t st);
 hipError_t launch_wgrad(int variant, const WgradParams& P, hipStream_t st);

@@ -17,6 +17,7 @@
 //
 // 64-byte granules of a tile row are XOR-swizzled with the row number (applied on the global
 // side by choosing which chunk a lane fetches) so the transposing reads are conflict-free.
+#include <type_traits>
 #include "common.h"
 #include "wgrad.h"
 #include "dma.h"
@@ -28,18 +29,22 @@ namespace sdconv {
 typedef _Float16 half8 __attribute__((ext_vector_type(8)));
 typedef _Float16 half4 __attribute__((ext_vector_type(4)));
 typedef float float16v __attribute__((ext_vector_type(16)));
+typedef float float4w __attribute__((ext_vector_type(4)));
 
 // HF: only the upper half of the waves sends the loads (and then multiplies like the others).
 // With two waves per SIMD the lower wave keeps the matrix pipe busy while its partner is stalled
 // in the burst of LDS-DMA instructions, instead of both stalling at once (see igemm_ws.hip).
-template <int BM, int BN, int WGM, int WGN, int S, int BP, bool LINEAR, bool HF>
+// MF: 32 = v_mfma_f32_32x32x16_f16 blocks, 16 = v_mfma_f32_16x16x32_f16 blocks (measured faster
+// on the large tiles).
+template <int BM, int BN, int WGM, int WGN, int S, int BP, bool LINEAR, bool HF, int MF = 32>
 __global__ __launch_bounds__(64 * WGM * WGN) void wgrad_dma_kernel(WgradParams P)
 {
     constexpr int NW = WGM * WGN;
     constexpr int NWF = HF ? NW / 2 : NW, NT = 64 * NWF;    // fetching waves / threads
     constexpr int FW0 = NW - NWF;                           // first fetching wave
     constexpr int WM = BM / WGM, WN = BN / WGN;
-    constexpr int FM = WM / 32, FN = WN / 32;
+    constexpr int FM = WM / MF, FN = WN / MF;
+    constexpr int ACCN = MF == 32 ? 16 : 4, KSTEP = MF == 32 ? 16 : 32;
     constexpr int CRG = BM / 8, CRX = BN / 8;           // 16-byte chunks per tile row
     constexpr int RPG = NT / CRG, RPX = NT / CRX;       // rows one pass of all threads covers
     constexpr int PG = BP / RPG, PX = BP / RPX;         // DMA loads per thread and stage
@@ -47,7 +52,7 @@ __global__ __launch_bounds__(64 * WGM * WGN) void wgrad_dma_kernel(WgradParams P
     constexpr int INFLIGHT = (S - 2) * (PG + PX);
     constexpr int GMG = (BM * 2 >= 256) ? 3 : (BM * 2 / 64 - 1);
     constexpr int GMX = (BN * 2 >= 256) ? 3 : (BN * 2 / 64 - 1);
-    static_assert(WM % 32 == 0 && WN % 32 == 0, "wave tile");
+    static_assert((MF == 32 || MF == 16) && WM % MF == 0 && WN % MF == 0 && BP % KSTEP == 0, "wave tile");
     static_assert(PG >= 1 && PX >= 1 && BP % RPG == 0 && BP % RPX == 0 && RPG % 4 == 0 && RPX % 4 == 0, "staging");
     static_assert(S >= 2 && INFLIGHT < 64 && BP % 16 == 0 && BP <= 64 * NW, "pipeline");
 
@@ -137,44 +142,40 @@ __global__ __launch_bounds__(64 * WGM * WGN) void wgrad_dma_kernel(WgradParams P
         }
     };
 
-    float16v acc[FM][FN];
+    typedef typename std::conditional<MF == 32, float16v, float4w>::type acc_t;
+    acc_t acc[FM][FN];
 #pragma unroll
     for (int a = 0; a < FM; ++a)
 #pragma unroll
         for (int c = 0; c < FN; ++c)
 #pragma unroll
-            for (int e = 0; e < 16; ++e) acc[a][c][e] = 0.f;
-
-    const int grp = lane >> 4, gl = lane & 15;
-    const int frag_row = 8 * (grp >> 1) + (gl >> 2);
-    const int frag_col = 16 * (grp & 1) + 4 * (gl & 3);
+            for (int e = 0; e < ACCN; ++e) acc[a][c][e] = 0.f;
 
     auto compute = [&](int stage) {
         const unsigned char* sg = smem + stage * STAGE;
         const unsigned char* sx = sg + GBYTES;
 #pragma unroll
-        for (int kk = 0; kk < BP / 16; ++kk) {
+        for (int kk = 0; kk < BP / KSTEP; ++kk) {
             half8 fa[FM], fb[FN];
-            const int row = kk * 16 + frag_row;
 #pragma unroll
             for (int a = 0; a < FM; ++a) {
-                int col = wm * WM + a * 32 + frag_col;
-                half4 lo = lds_read_tr16(sg + sw_off<BM>(row, col));
-                half4 hi = lds_read_tr16(sg + sw_off<BM>(row + 4, col));
-                fa[a] = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+                if (MF == 32) fa[a] = lds_frag_tr<BM>(sg, kk * 16, wm * WM + a * 32, lane);
+                else fa[a] = lds_frag_tr_16<BM>(sg, kk * 32, wm * WM + a * 16, lane);
             }
 #pragma unroll
             for (int c = 0; c < FN; ++c) {
-                int col = wn * WN + c * 32 + frag_col;
-                half4 lo = lds_read_tr16(sx + sw_off<BN>(row, col));
-                half4 hi = lds_read_tr16(sx + sw_off<BN>(row + 4, col));
-                fb[c] = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+                if (MF == 32) fb[c] = lds_frag_tr<BN>(sx, kk * 16, wn * WN + c * 32, lane);
+                else fb[c] = lds_frag_tr_16<BN>(sx, kk * 32, wn * WN + c * 16, lane);
             }
 #pragma unroll
             for (int a = 0; a < FM; ++a)
 #pragma unroll
-                for (int c = 0; c < FN; ++c)
-                    acc[a][c] = __builtin_amdgcn_mfma_f32_32x32x16_f16(fa[a], fb[c], acc[a][c], 0, 0, 0);
+                for (int c = 0; c < FN; ++c) {
+                    if constexpr (MF == 32)
+                        acc[a][c] = __builtin_amdgcn_mfma_f32_32x32x16_f16(fa[a], fb[c], acc[a][c], 0, 0, 0);
+                    else
+                        acc[a][c] = __builtin_amdgcn_mfma_f32_16x16x32_f16(fa[a], fb[c], acc[a][c], 0, 0, 0);
+                }
         }
     };
 
@@ -206,25 +207,26 @@ __global__ __launch_bounds__(64 * WGM * WGN) void wgrad_dma_kernel(WgradParams P
         }
     }
 
-    // ---- store the fp32 tile: lanes 0..31 hold consecutive channels of one filter row ------
+    // ---- store the fp32 tile: lanes 0..MF-1 hold consecutive channels of one filter row -----
     const long numel = (long)P.K * P.R * P.S * P.C;
     float* out = P.out + (long)split * numel;
-    const int l32 = lane & 31, lhi = lane >> 5;
+    const int lcol = lane & (MF - 1), lhi = lane / MF;
 #pragma unroll
     for (int a = 0; a < FM; ++a)
 #pragma unroll
         for (int c = 0; c < FN; ++c) {
-            int col = c0 + wn * WN + c * 32 + l32;
+            int col = c0 + wn * WN + c * MF + lcol;
             if (col >= P.C) continue;
 #pragma unroll
-            for (int e = 0; e < 16; ++e) {
-                int k = k0 + wm * WM + a * 32 + 8 * (e >> 2) + 4 * lhi + (e & 3);
+            for (int e = 0; e < ACCN; ++e) {
+                int k = (MF == 32) ? k0 + wm * WM + a * 32 + 8 * (e >> 2) + 4 * lhi + (e & 3)
+                                   : k0 + wm * WM + a * 16 + 4 * lhi + e;
                 if (k < P.K) out[((long)k * P.R * P.S + tap) * P.C + col] = acc[a][c][e];
             }
         }
 }
 
-template <int BM, int BN, int WGM, int WGN, int S, int BP, bool HF = false>
+template <int BM, int BN, int WGM, int WGN, int S, int BP, bool HF = false, int MF = 32>
 static hipError_t launch_wdma(const WgradParams& P, hipStream_t st)
 {
     constexpr size_t lds = (size_t)S * BP * (BM + BN) * 2 + (size_t)S * BP * sizeof(unsigned);
@@ -233,21 +235,21 @@ static hipError_t launch_wdma(const WgradParams& P, hipStream_t st)
     static bool configured = false;
     if (!configured) {
         hipError_t e = hipFuncSetAttribute(
-            reinterpret_cast<const void*>(&wgrad_dma_kernel<BM, BN, WGM, WGN, S, BP, false, HF>),
+            reinterpret_cast<const void*>(&wgrad_dma_kernel<BM, BN, WGM, WGN, S, BP, false, HF, MF>),
             hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         if (e != hipSuccess) return e;
         e = hipFuncSetAttribute(
-            reinterpret_cast<const void*>(&wgrad_dma_kernel<BM, BN, WGM, WGN, S, BP, true, HF>),
+            reinterpret_cast<const void*>(&wgrad_dma_kernel<BM, BN, WGM, WGN, S, BP, true, HF, MF>),
             hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         if (e != hipSuccess) return e;
         configured = true;
     }
     long blocks = (long)P.tiles_c * P.tiles_k * P.R * P.S * P.splits;
     if (linear)
-        hipLaunchKernelGGL((wgrad_dma_kernel<BM, BN, WGM, WGN, S, BP, true, HF>), dim3((unsigned)blocks),
+        hipLaunchKernelGGL((wgrad_dma_kernel<BM, BN, WGM, WGN, S, BP, true, HF, MF>), dim3((unsigned)blocks),
                            dim3(64 * WGM * WGN), lds, st, P);
     else
-        hipLaunchKernelGGL((wgrad_dma_kernel<BM, BN, WGM, WGN, S, BP, false, HF>), dim3((unsigned)blocks),
+        hipLaunchKernelGGL((wgrad_dma_kernel<BM, BN, WGM, WGN, S, BP, false, HF, MF>), dim3((unsigned)blocks),
                            dim3(64 * WGM * WGN), lds, st, P);
     return hipGetLastError();
 }
@@ -267,6 +269,13 @@ const WgradVariant kWgradDmaVariants[kNumWgradDmaVariants] = {
     {256, 128, "wgrad_dma_256x128x32_8w_s3_hf"},
     {128, 128, "wgrad_dma_128x128x64_8w_s3_hf"},
     {256, 128, "wgrad_dma_256x128x64_8w_s3_hf"},
+    {256, 256, "wgrad_dma_256x256x64_8w_s2_hf_m16"},
+    {256, 256, "wgrad_dma_256x256x32_8w_s3_hf_m16"},
+    {128, 128, "wgrad_dma_128x128x64_8w_s3_hf_m16"},
+    {256, 128, "wgrad_dma_256x128x64_8w_s3_hf_m16"},
+    {64, 64, "wgrad_dma_64x64x64_4w_s3_m16"},
+    {128, 128, "wgrad_dma_128x128x64_4w_s2_m16"},
+    {64, 128, "wgrad_dma_64x128x64_4w_s3_m16"},
 };
 
 hipError_t launch_wgrad_dma(int variant, const WgradParams& P, hipStream_t st)
@@ -286,6 +295,13 @@ hipError_t launch_wgrad_dma(int variant, const WgradParams& P, hipStream_t st)
         case 11: return launch_wdma<256, 128, 4, 2, 3, 32, true>(P, st);
         case 12: return launch_wdma<128, 128, 2, 4, 3, 64, true>(P, st);
         case 13: return launch_wdma<256, 128, 4, 2, 3, 64, true>(P, st);
+        case 14: return launch_wdma<256, 256, 2, 4, 2, 64, true, 16>(P, st);
+        case 15: return launch_wdma<256, 256, 2, 4, 3, 32, true, 16>(P, st);
+        case 16: return launch_wdma<128, 128, 2, 4, 3, 64, true, 16>(P, st);
+        case 17: return launch_wdma<256, 128, 4, 2, 3, 64, true, 16>(P, st);
+        case 18: return launch_wdma<64, 64, 2, 2, 3, 64, false, 16>(P, st);
+        case 19: return launch_wdma<128, 128, 2, 2, 2, 64, false, 16>(P, st);
+        case 20: return launch_wdma<64, 128, 1, 4, 3, 64, false, 16>(P, st);
         default: return hipErrorInvalidValue;
     }
 }
