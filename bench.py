@@ -238,6 +238,36 @@ def main() -> int:
         pass
     unscale_gbs = 8.0 * dw_total / unscale_ms / 1e6
 
+    # ---- side figures ---------------------------------------------------------------------------
+    # the nominal "~25M" gradient buffer of the workload description (24 * 2^20 elements)
+    n_nom = 24 << 20
+    g_nom = torch.randn(n_nom, dtype=torch.float32, device=dev)
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    for _ in range(2):
+        sd.grad_unscale_check(g_nom, n_nom, inv_scale, flag, stream)
+    e0.record()
+    for _ in range(5):
+        sd.grad_unscale_check(g_nom, n_nom, inv_scale, flag, stream)
+    e1.record()
+    torch.cuda.synchronize()
+    nom_ms = e0.elapsed_time(e1) / 5
+    del g_nom
+    # what the matrix pipes sustain with nothing else in the way (see sdconv_mfma_ceiling)
+    props = torch.cuda.get_device_properties(dev)
+    cus = props.multi_processor_count
+    blocks, iters = 4 * cus, 4000
+    scratch = torch.empty(blocks * 512, dtype=torch.float32, device=dev)
+    sd.sdconv_mfma_ceiling(scratch, blocks, 50, stream)
+    e0.record()
+    sd.sdconv_mfma_ceiling(scratch, blocks, iters, stream)
+    e1.record()
+    torch.cuda.synchronize()
+    ceiling_tflops = blocks * 8 * iters * 16 * 32768.0 / (e0.elapsed_time(e1) * 1e-3) / 1e12
+    del scratch
+    # the stem's data gradient is never needed in training (there is no gradient w.r.t. the image)
+    stem_dgrad_ms = sum(p["us"] for p in per_call if p["layer"] == "stem" and p["pass"] == "dgrad") / 1e3
+    stem_flops = next(l.flops for l in layers if l.name == "stem")
+
     # ---- the named target layers: 3x3 convs of res3/res4 ----------------------------------------
     targets = [p for p in per_call if p["layer"].endswith("b") and p["layer"].startswith(("res3", "res4"))]
     tgt_flops = sum(next(l.flops for l in layers if l.name == p["layer"]) for p in targets)
@@ -259,7 +289,12 @@ def main() -> int:
         "roofline": roofline,
         "unscale": {"us": unscale_ms * 1e3, "GBps": unscale_gbs, "frac_hbm": unscale_gbs / PEAK_HBM_GBS,
                     "bytes": 8 * dw_total},
+        "unscale_nominal_25M": {"elements": n_nom, "us": nom_ms * 1e3, "GBps": 8.0 * n_nom / nom_ms / 1e6},
+        "device": {"name": props.name, "compute_units": cus, "mfma_only_tflops": ceiling_tflops, "mfma_only_frac_of_peak": ceiling_tflops / PEAK_F16_TFLOPS},
         "ms_per_step_with_events": instrumented_ms,
+        "one_stream_events": {"tflops": flops_per_step / instrumented_ms / 1e9,
+                              "tflops_without_stem_dgrad": (flops_per_step - stem_flops)
+                              / (instrumented_ms - stem_dgrad_ms) / 1e9},
         "kernels": {k: {"ms_per_step": g["ms"], "launches": g["launches"],
                         "tflops": g["flops"] / g["ms"] / 1e9} for k, g in sorted(groups.items())},
         "paper_context": "Fig. 1(b): 2.0x FP32->FP16 end-to-end training speedup, hardware not stated",

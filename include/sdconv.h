@@ -106,6 +106,15 @@ int sdconv_last_hip_error(void);
  * Static string; "invalid" for a bad descriptor. */
 const char *sdconv_kernel_name(const conv2d_desc *desc, int pass);
 
+/* Measurement aid, not part of the convolution path: launches `blocks` workgroups of 8 waves
+ * that each issue iters * 16 v_mfma_f32_32x32x16_f16 on registers only (32768 FLOP per
+ * instruction and wave), i.e. blocks * 8 * iters * 16 * 32768 FLOP in total.  Timed by the
+ * caller, it gives the fp16 matrix rate the device sustains (the clock under matrix load is
+ * below the spec-sheet clock).  scratch: device buffer of at least blocks * 512 floats,
+ * overwritten.  Asynchronous on hip_stream.  SDCONV_EINVAL for a null buffer or non-positive
+ * counts. */
+int sdconv_mfma_ceiling(float *scratch, int blocks, int iters, void *hip_stream);
+
 #ifdef __cplusplus
 }
 #endif

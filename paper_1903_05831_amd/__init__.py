@@ -21,6 +21,7 @@ FWD, DGRAD, WGRAD = 0, 1, 2
 EXPORTS = (
     "conv2d_out_shape", "conv2d_workspace_bytes", "conv2d_fwd", "conv2d_dgrad", "conv2d_wgrad",
     "grad_unscale_check", "sdconv_status_string", "sdconv_last_hip_error", "sdconv_kernel_name",
+    "sdconv_mfma_ceiling",
 )
 
 
@@ -65,6 +66,8 @@ def lib() -> ctypes.CDLL:
         L.sdconv_last_hip_error.restype = ctypes.c_int
         L.sdconv_kernel_name.argtypes = [dp, ctypes.c_int]
         L.sdconv_kernel_name.restype = ctypes.c_char_p
+        L.sdconv_mfma_ceiling.argtypes = [vp, ctypes.c_int, ctypes.c_int, vp]
+        L.sdconv_mfma_ceiling.restype = ctypes.c_int
         _lib = L
     return _lib
 
@@ -137,6 +140,12 @@ def conv2d_dgrad(desc, dy, w, dx, workspace=None, stream: int = 0) -> None:
 
 def conv2d_wgrad(desc, x, dy, dw, workspace=None, stream: int = 0) -> None:
     _call("conv2d_wgrad", desc, x, dy, dw, workspace, stream)
+
+
+def sdconv_mfma_ceiling(scratch, blocks: int, iters: int, stream: int = 0) -> None:
+    rc = lib().sdconv_mfma_ceiling(_ptr(scratch), blocks, iters, stream or 0)
+    if rc:
+        raise SdconvError(rc, "sdconv_mfma_ceiling")
 
 
 def grad_unscale_check(grad, n: int, inv_scale: float, found_nonfinite, stream: int = 0) -> None:

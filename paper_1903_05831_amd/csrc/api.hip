@@ -149,3 +149,14 @@ extern "C" __attribute__((visibility("default"))) const char* sdconv_kernel_name
         default: return "invalid";
     }
 }
+
+namespace sdconv { hipError_t launch_mfma_ceiling(float* out, int blocks, int iters, hipStream_t st); }
+
+extern "C" __attribute__((visibility("default"))) int sdconv_mfma_ceiling(float* scratch, int blocks, int iters,
+                                                                          void* hip_stream)
+{
+    if (!scratch || blocks <= 0 || iters <= 0) return SDCONV_EINVAL;
+    hipError_t e = sdconv::launch_mfma_ceiling(scratch, blocks, iters, static_cast<hipStream_t>(hip_stream));
+    if (e != hipSuccess) { g_last_hip_error = (int)e; return SDCONV_EHIP; }
+    return SDCONV_OK;
+}
