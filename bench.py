@@ -252,6 +252,28 @@ def main() -> int:
     torch.cuda.synchronize()
     nom_ms = e0.elapsed_time(e1) / 5
     del g_nom
+    # the optimizer tail that follows the check (not part of `value`): dynamic unscale, then the
+    # SGD-momentum update with the fp16 weight cast and the loss-scale transition, on the
+    # workload's 23 454 912 weights
+    mw = torch.randn(dw_total, dtype=torch.float32, device=dev) * 0.05
+    mbuf = torch.zeros(dw_total, dtype=torch.float32, device=dev)
+    w16 = torch.empty(dw_total, dtype=torch.float16, device=dev)
+    ls_state = torch.tensor([1149239296, 0], dtype=torch.int32, device=dev)     # {scale = 1024.0f, good_steps = 0}
+
+    def tail():
+        sd.grad_unscale_check_dynamic(dw_flat, dw_total, ls_state, flag, stream)
+        sd.sgd_momentum_update(mw, mbuf, dw_flat, w16, dw_total, 0.02, 0.9, 1e-4, flag, ls_state,
+                               2.0, 0.5, 2000, stream)
+    dw_flat.normal_()
+    for _ in range(2):
+        tail()
+    e0.record()
+    for _ in range(5):
+        tail()
+    e1.record()
+    torch.cuda.synchronize()
+    tail_ms = e0.elapsed_time(e1) / 5
+    del mw, mbuf, w16
     # what the matrix pipes sustain with nothing else in the way (see sdconv_mfma_ceiling)
     props = torch.cuda.get_device_properties(dev)
     cus = props.multi_processor_count
@@ -290,6 +312,10 @@ def main() -> int:
         "unscale": {"us": unscale_ms * 1e3, "GBps": unscale_gbs, "frac_hbm": unscale_gbs / PEAK_HBM_GBS,
                     "bytes": 8 * dw_total},
         "unscale_nominal_25M": {"elements": n_nom, "us": nom_ms * 1e3, "GBps": 8.0 * n_nom / nom_ms / 1e6},
+        "optimizer_tail": {"what": "grad_unscale_check_dynamic + sgd_momentum_update on %d weights" % dw_total,
+                           "us": tail_ms * 1e3, "bytes": 30 * dw_total,
+                           "GBps": 30.0 * dw_total / tail_ms / 1e6,
+                           "frac_hbm": 30.0 * dw_total / tail_ms / 1e6 / PEAK_HBM_GBS},
         "device": {"name": props.name, "compute_units": cus, "mfma_only_tflops": ceiling_tflops, "mfma_only_frac_of_peak": ceiling_tflops / PEAK_F16_TFLOPS},
         "ms_per_step_with_events": instrumented_ms,
         "one_stream_events": {"tflops": flops_per_step / instrumented_ms / 1e9,

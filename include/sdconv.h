@@ -96,6 +96,43 @@ int conv2d_wgrad(const conv2d_desc *desc, const void *x, const void *dy, float *
 int grad_unscale_check(float *grad, size_t n, float inv_scale, int32_t *found_nonfinite,
                        void *hip_stream);
 
+/* ---- optimizer tail (the step right after the overflow check) ------------------------------
+ * Section 2.2 of the paper adopts the loss scaling of its cited mixed-precision recipe; the
+ * scale schedule and the optimizer are not spelled out there.  Taken here: the dynamic
+ * schedule of that recipe and SGD with momentum on fp32 master weights in the formulation of
+ * the framework the paper builds on. */
+
+/* Loss-scale state in DEVICE memory (4-byte aligned), owned by the caller. */
+typedef struct {
+    float scale;         /* current loss scale S */
+    int32_t good_steps;  /* steps without overflow since the scale last changed */
+} loss_scale_state;
+
+/* grad_unscale_check with inv_scale = 1 / state->scale read on the device (one correctly
+ * rounded binary32 division), so that the scale never has to visit the host.  state is only
+ * read.  Same alignment, ownership and error rules as grad_unscale_check. */
+int grad_unscale_check_dynamic(float *grad, size_t n, const loss_scale_state *state,
+                               int32_t *found_nonfinite, void *hip_stream);
+
+/* One optimizer step over n elements of flat device buffers, then one loss-scale transition.
+ *   if *found_nonfinite == 0, for every i (each operation a separate binary32 operation):
+ *       momentum_buf[i] <- momentum*momentum_buf[i] - lr*(grad[i] + weight_decay*master_w[i])
+ *       master_w[i]     <- master_w[i] + momentum_buf[i]
+ *   else master_w and momentum_buf are left untouched (the step is skipped);
+ *   always: w_half[i] <- binary16(master_w[i]), round to nearest even (n halves, 8-byte aligned);
+ *   then:   flag set -> state->scale *= backoff, good_steps = 0;
+ *           else ++good_steps, and when it reaches interval: scale *= growth, good_steps = 0.
+ * grad is the UNSCALED gradient (after grad_unscale_check*), read only.  master_w,
+ * momentum_buf and grad are 16-byte aligned fp32; found_nonfinite and state are device
+ * pointers, the flag is only read.  Asynchronous on hip_stream; no host synchronisation.
+ * SDCONV_EINVAL: null pointers (with n > 0), misalignment, non-finite lr / momentum /
+ * weight_decay, growth or backoff not finite and > 0, interval < 1.  n = 0 only advances the
+ * state. */
+int sgd_momentum_update(float *master_w, float *momentum_buf, const float *grad, void *w_half,
+                        size_t n, float lr, float momentum, float weight_decay,
+                        const int32_t *found_nonfinite, loss_scale_state *state, float growth,
+                        float backoff, int32_t interval, void *hip_stream);
+
 /* Static, human-readable text for a status code. */
 const char *sdconv_status_string(int status);
 

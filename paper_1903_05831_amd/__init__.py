@@ -21,7 +21,7 @@ FWD, DGRAD, WGRAD = 0, 1, 2
 EXPORTS = (
     "conv2d_out_shape", "conv2d_workspace_bytes", "conv2d_fwd", "conv2d_dgrad", "conv2d_wgrad",
     "grad_unscale_check", "sdconv_status_string", "sdconv_last_hip_error", "sdconv_kernel_name",
-    "sdconv_mfma_ceiling",
+    "sdconv_mfma_ceiling", "grad_unscale_check_dynamic", "sgd_momentum_update",
 )
 
 
@@ -66,6 +66,11 @@ def lib() -> ctypes.CDLL:
         L.sdconv_last_hip_error.restype = ctypes.c_int
         L.sdconv_kernel_name.argtypes = [dp, ctypes.c_int]
         L.sdconv_kernel_name.restype = ctypes.c_char_p
+        L.grad_unscale_check_dynamic.argtypes = [vp, sz, vp, vp, vp]
+        L.grad_unscale_check_dynamic.restype = ctypes.c_int
+        f32 = ctypes.c_float
+        L.sgd_momentum_update.argtypes = [vp, vp, vp, vp, sz, f32, f32, f32, vp, vp, f32, f32, ctypes.c_int32, vp]
+        L.sgd_momentum_update.restype = ctypes.c_int
         L.sdconv_mfma_ceiling.argtypes = [vp, ctypes.c_int, ctypes.c_int, vp]
         L.sdconv_mfma_ceiling.restype = ctypes.c_int
         _lib = L
@@ -140,6 +145,23 @@ def conv2d_dgrad(desc, dy, w, dx, workspace=None, stream: int = 0) -> None:
 
 def conv2d_wgrad(desc, x, dy, dw, workspace=None, stream: int = 0) -> None:
     _call("conv2d_wgrad", desc, x, dy, dw, workspace, stream)
+
+
+def grad_unscale_check_dynamic(grad, n: int, state, found_nonfinite, stream: int = 0) -> None:
+    """state: device tensor holding a loss_scale_state {float scale; int32 good_steps}."""
+    rc = lib().grad_unscale_check_dynamic(_ptr(grad), n, _ptr(state), _ptr(found_nonfinite), stream or 0)
+    if rc:
+        raise SdconvError(rc, "grad_unscale_check_dynamic")
+
+
+def sgd_momentum_update(master_w, momentum_buf, grad, w_half, n: int, lr: float, momentum: float,
+                        weight_decay: float, found_nonfinite, state, growth: float, backoff: float,
+                        interval: int, stream: int = 0) -> None:
+    rc = lib().sgd_momentum_update(_ptr(master_w), _ptr(momentum_buf), _ptr(grad), _ptr(w_half), n,
+                                   lr, momentum, weight_decay, _ptr(found_nonfinite), _ptr(state),
+                                   growth, backoff, interval, stream or 0)
+    if rc:
+        raise SdconvError(rc, "sgd_momentum_update")
 
 
 def sdconv_mfma_ceiling(scratch, blocks: int, iters: int, stream: int = 0) -> None:

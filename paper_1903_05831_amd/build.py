@@ -18,6 +18,11 @@ FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fvisibility=hidden", "-
          "-I", os.path.join(ROOT, "include"), "-I", CSRC]
 
 
+# Files whose arithmetic is defined operation by operation (one rounding each): no contraction
+# of a*b + c into a fused multiply-add, which is the compiler's default for device code.
+EXTRA_FLAGS = {"optimizer.hip": ["-ffp-contract=off"], "unscale.hip": ["-ffp-contract=off"]}
+
+
 def sources():
     return sorted(glob.glob(os.path.join(CSRC, "*.hip")))
 
@@ -39,7 +44,8 @@ def build(force: bool = True, verbose: bool = False) -> str:
     os.makedirs(bdir, exist_ok=True)
     for src in sources():
         obj = os.path.join(bdir, os.path.basename(src) + ".o")
-        cmd = [HIPCC] + [f for f in FLAGS if f != "-shared"] + ["-c", src, "-o", obj]
+        cmd = ([HIPCC] + [f for f in FLAGS if f != "-shared"] + EXTRA_FLAGS.get(os.path.basename(src), [])
+               + ["-c", src, "-o", obj])
         if verbose:
             print(" ".join(cmd))
         procs.append((src, subprocess.Popen(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)))

@@ -120,7 +120,43 @@ extern "C" __attribute__((visibility("default"))) int grad_unscale_check(float* 
     if (reinterpret_cast<uintptr_t>(found_nonfinite) & 3u) return SDCONV_EINVAL;
     if (!isfinite(inv_scale) || !(inv_scale > 0.f)) return SDCONV_EINVAL;
     if (n >= ((size_t)1 << 40)) return SDCONV_EINVAL;
-    return hip_status(launch_unscale_check(grad, n, inv_scale, found_nonfinite, (hipStream_t)hip_stream));
+    return hip_status(launch_unscale_check(grad, n, inv_scale, nullptr, found_nonfinite, (hipStream_t)hip_stream));
+}
+
+extern "C" __attribute__((visibility("default"))) int grad_unscale_check_dynamic(float* grad, size_t n,
+                                                                                 const loss_scale_state* state,
+                                                                                 int32_t* found_nonfinite,
+                                                                                 void* hip_stream)
+{
+    if (!found_nonfinite || !state) return SDCONV_EINVAL;
+    if (n > 0 && !grad) return SDCONV_EINVAL;
+    if (reinterpret_cast<uintptr_t>(grad) & 3u) return SDCONV_EINVAL;
+    if ((reinterpret_cast<uintptr_t>(found_nonfinite) & 3u) || (reinterpret_cast<uintptr_t>(state) & 3u))
+        return SDCONV_EINVAL;
+    if (n >= ((size_t)1 << 40)) return SDCONV_EINVAL;
+    return hip_status(launch_unscale_check(grad, n, 1.0f, &state->scale, found_nonfinite, (hipStream_t)hip_stream));
+}
+
+extern "C" __attribute__((visibility("default"))) int sgd_momentum_update(
+    float* master_w, float* momentum_buf, const float* grad, void* w_half, size_t n, float lr, float momentum,
+    float weight_decay, const int32_t* found_nonfinite, loss_scale_state* state, float growth, float backoff,
+    int32_t interval, void* hip_stream)
+{
+    if (!found_nonfinite || !state) return SDCONV_EINVAL;
+    if (n > 0 && (!master_w || !momentum_buf || !grad || !w_half)) return SDCONV_EINVAL;
+    if ((reinterpret_cast<uintptr_t>(master_w) | reinterpret_cast<uintptr_t>(momentum_buf) |
+         reinterpret_cast<uintptr_t>(grad)) & 15u)
+        return SDCONV_EINVAL;
+    if (reinterpret_cast<uintptr_t>(w_half) & 7u) return SDCONV_EINVAL;
+    if ((reinterpret_cast<uintptr_t>(found_nonfinite) & 3u) || (reinterpret_cast<uintptr_t>(state) & 3u))
+        return SDCONV_EINVAL;
+    if (!isfinite(lr) || !isfinite(momentum) || !isfinite(weight_decay)) return SDCONV_EINVAL;
+    if (!isfinite(growth) || !isfinite(backoff) || !(growth > 0.f) || !(backoff > 0.f) || interval < 1)
+        return SDCONV_EINVAL;
+    if (n >= ((size_t)1 << 40)) return SDCONV_EINVAL;
+    return hip_status(launch_sgd_momentum(master_w, momentum_buf, grad, w_half, n, lr, momentum, weight_decay,
+                                          found_nonfinite, state, growth, backoff, interval,
+                                          (hipStream_t)hip_stream));
 }
 
 extern "C" __attribute__((visibility("default"))) const char* sdconv_status_string(int status)

@@ -45,6 +45,10 @@ hipError_t run_wgrad(const Geom& g, const Plan& p, const __half* x, const __half
 hipError_t launch_direct_fwd(const Geom& g, const __half* x, const __half* w, __half* y, hipStream_t st);
 hipError_t launch_direct_dgrad(const Geom& g, const __half* dy, const __half* w, __half* dx, hipStream_t st);
 hipError_t launch_direct_wgrad(const Geom& g, const __half* x, const __half* dy, float* dw, hipStream_t st);
-hipError_t launch_unscale_check(float* grad, size_t n, float inv_scale, int32_t* flag, hipStream_t st);
+hipError_t launch_unscale_check(float* grad, size_t n, float inv_scale, const float* scale_on_device,
+                                int32_t* flag, hipStream_t st);
+hipError_t launch_sgd_momentum(float* w, float* mom, const float* g, void* w16, size_t n, float lr, float mu,
+                               float wd, const int32_t* flag, void* state, float growth, float backoff,
+                               int32_t interval, hipStream_t st);
 
 }  // namespace sdconv

@@ -18,11 +18,14 @@ __device__ __forceinline__ unsigned nonfinite_bits(float v)
 
 __global__ void clear_flag_kernel(int32_t* flag) { *flag = 0; }
 
+// scale_on_device: nullptr, or the current loss scale in device memory: inv_scale is then
+// 1/scale, one correctly rounded binary32 division.
 __global__ __launch_bounds__(kUnscaleThreads) void unscale_check_kernel(
     float* __restrict__ grad, size_t n, size_t head, size_t nvec, float inv_scale,
-    int32_t* __restrict__ flag)
+    const float* __restrict__ scale_on_device, int32_t* __restrict__ flag)
 {
     typedef float float4v __attribute__((ext_vector_type(4)));
+    if (scale_on_device) inv_scale = __fdiv_rn(1.0f, *scale_on_device);
     unsigned bad = 0;
     float4v* body = reinterpret_cast<float4v*>(grad + head);
     size_t base = (size_t)blockIdx.x * (kUnscaleThreads * kUnscaleVecPerThread) + threadIdx.x;
@@ -65,7 +68,8 @@ __global__ __launch_bounds__(kUnscaleThreads) void unscale_check_kernel(
     if (any != 0ull && (threadIdx.x & 63) == 0) atomicOr(flag, 1);
 }
 
-hipError_t launch_unscale_check(float* grad, size_t n, float inv_scale, int32_t* flag, hipStream_t st)
+hipError_t launch_unscale_check(float* grad, size_t n, float inv_scale, const float* scale_on_device,
+                                int32_t* flag, hipStream_t st)
 {
     hipLaunchKernelGGL(clear_flag_kernel, dim3(1), dim3(1), 0, st, flag);
     hipError_t e = hipGetLastError();
@@ -78,7 +82,7 @@ hipError_t launch_unscale_check(float* grad, size_t n, float inv_scale, int32_t*
     size_t blocks = (nvec + per_block - 1) / per_block;
     if (blocks == 0) blocks = 1;
     hipLaunchKernelGGL(unscale_check_kernel, dim3((unsigned)blocks), dim3(kUnscaleThreads), 0, st,
-                       grad, n, head, nvec, inv_scale, flag);
+                       grad, n, head, nvec, inv_scale, scale_on_device, flag);
     return hipGetLastError();
 }
 

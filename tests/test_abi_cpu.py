@@ -110,6 +110,27 @@ def test_unscale_argument_checks():
         assert L.grad_unscale_check(ok, 16, ctypes.c_float(bad), ok, None) == sd.EINVAL
 
 
+def test_optimizer_tail_argument_checks():
+    """Nothing is launched for a bad argument (there is no GPU here: a launch would fail differently)."""
+    L = sd.lib()
+    ok = 0x1000
+    f = ctypes.c_float
+    inf, nan = float("inf"), float("nan")
+    assert L.grad_unscale_check_dynamic(ok, 16, None, ok, None) == sd.EINVAL
+    assert L.grad_unscale_check_dynamic(ok, 16, ok, None, None) == sd.EINVAL
+    assert L.grad_unscale_check_dynamic(None, 16, ok, ok, None) == sd.EINVAL
+    assert L.grad_unscale_check_dynamic(ok + 2, 16, ok, ok, None) == sd.EINVAL
+
+    def upd(w=ok, m=ok, g=ok, h=ok, n=16, lr=0.1, mu=0.9, wd=0.0, flag=ok, st=ok, gr=2.0, bo=0.5, iv=2000):
+        return L.sgd_momentum_update(w, m, g, h, n, f(lr), f(mu), f(wd), flag, st, f(gr), f(bo), iv, None)
+
+    for kw in (dict(w=None), dict(m=None), dict(g=None), dict(h=None), dict(flag=None), dict(st=None),
+               dict(w=ok + 4), dict(m=ok + 8), dict(g=ok + 4), dict(h=ok + 2), dict(flag=ok + 1), dict(st=ok + 2),
+               dict(lr=nan), dict(mu=inf), dict(wd=nan), dict(gr=0.0), dict(gr=inf), dict(bo=-1.0), dict(bo=nan),
+               dict(iv=0)):
+        assert upd(**kw) == sd.EINVAL, kw
+
+
 def test_status_strings():
     assert sd.status_string(sd.OK) == "ok"
     for code in (sd.EINVAL, sd.EUNSUPPORTED, sd.EWORKSPACE, sd.EHIP, 99):
