@@ -32,21 +32,33 @@ typedef float float16v __attribute__((ext_vector_type(16)));
 typedef float float4p __attribute__((ext_vector_type(4)));
 
 // MF: 32 = v_mfma_f32_32x32x16_f16 blocks, 16 = v_mfma_f32_16x16x32_f16 blocks.
-template <int MODE, int TH, int TW, int BN, int WGM, int WGN, int SB, int MF = 32>
+// NIW: number of fetching waves (the last NIW of the WGM x WGN waves); 0 = half of them.
+// TH*TW need not be a multiple of the MFMA block height: the GEMM rows are padded up to
+// WGM*MF and the padding rows are multiplied but never stored.  10 x 14 blocks tile the
+// 100 x 168 and 50 x 84 feature maps of the res3 / res4 stages exactly (240 workgroups for
+// 256 CUs with 128- resp. 64-wide filter tiles).
+// TPS: taps per pipeline step (must divide R*S).  A step of one tap is only 64 deep; on small
+// tiles the barrier and the wait then cost as much as the MFMAs between them, so a step can
+// cover a whole filter row (TPS = 3): the ring stage holds TPS filter slabs.
+template <int MODE, int TH, int TW, int BN, int WGM, int WGN, int SB, int MF = 32, int NIW = 0, int TPS = 1>
 __global__ __launch_bounds__(64 * WGM * WGN) void conv_patch_kernel(IgemmParams P)
 {
     constexpr int EH = 2, EW = 2;                   // extra patch rows / columns
     constexpr int PH = TH + EH, PW = TW + EW, PPX = PH * PW;
-    constexpr int NW = WGM * WGN, NI = NW / 2, IW0 = NW / 2;
-    constexpr int BM = TH * TW, WM = BM / WGM, WN = BN / WGN;
+    constexpr int NW = WGM * WGN, NI = NIW ? NIW : NW / 2, IW0 = NW - NI;
+    constexpr int BM = TH * TW;                             // output pixels of the block
+    constexpr int BMP = (BM + MF * WGM - 1) / (MF * WGM) * (MF * WGM);   // GEMM rows incl. padding
+    constexpr int WM = BMP / WGM, WN = BN / WGN;
     constexpr int FM = WM / MF, FN = WN / MF;
     constexpr int ACCN = MF == 32 ? 16 : 4, KSTEP = MF == 32 ? 16 : 32, CPK = KSTEP / 8;
     constexpr int NPL = (PPX + 8 * NI - 1) / (8 * NI);     // patch loads per fetching lane
     constexpr int PATCHB = NPL * NI * 1024;                // bytes of one patch buffer
-    constexpr int PB = BN / (8 * NI);                      // filter loads per fetching lane and tap
-    constexpr int BSTAGE = BN * 128;
+    constexpr int PB1 = BN / (8 * NI);                     // filter loads per fetching lane and tap
+    constexpr int PB = TPS * PB1;                          // ... and step
+    constexpr int BSLAB = BN * 128;                        // one tap's filter slab
+    constexpr int BSTAGE = TPS * BSLAB;
     constexpr int D = SB - 1;                              // filter stages in flight
-    static_assert((MF == 32 || MF == 16) && NW % 2 == 0 && WM % MF == 0 && WN % MF == 0 && BN % (8 * NI) == 0, "tile shape");
+    static_assert((MF == 32 || MF == 16) && NI >= 1 && NI < NW && WM % MF == 0 && WN % MF == 0 && BN % (8 * NI) == 0, "tile shape");
     static_assert(SB >= 2 && NPL + D * PB < 64, "loads in flight");   // vmcnt is a 6-bit counter
 
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
@@ -84,13 +96,14 @@ __global__ __launch_bounds__(64 * WGM * WGN) void conv_patch_kernel(IgemmParams 
     }
     __syncthreads();
     const int kchunks = P.Cs / 64;
-    const int nk = ntaps * kchunks;
+    const int ngroups = ntaps / TPS;                // steps per channel slab
+    const int nk = ngroups * kchunks;
 
     // ---- fetching side ---------------------------------------------------------------------
     const bool fetcher = wave >= IW0;
     const int fw = wave - IW0;
     const int fpix = lane >> 3, fslot = lane & 7;   // pixel (or filter row) within an instruction, chunk slot
-    unsigned a_off[NPL], b_off[PB];
+    unsigned a_off[NPL], b_off[PB1];
     if (fetcher) {
 #pragma unroll
         for (int q = 0; q < NPL; ++q) {
@@ -102,7 +115,7 @@ __global__ __launch_bounds__(64 * WGM * WGN) void conv_patch_kernel(IgemmParams 
             a_off[q] = ok ? (unsigned)((((n * P.Hs + hs) * P.Ws + ws) * P.Cs + kcl * 8) * 2) : kOutOfRange;
         }
 #pragma unroll
-        for (int p = 0; p < PB; ++p) {
+        for (int p = 0; p < PB1; ++p) {
             if (MODE == 0) {
                 const int row = (p * NI + fw) * 8 + fpix;
                 const int kcl = fslot ^ ((row >> 1) & 7);
@@ -126,17 +139,20 @@ __global__ __launch_bounds__(64 * WGM * WGN) void conv_patch_kernel(IgemmParams 
 #pragma unroll
         for (int q = 0; q < NPL; ++q) dma16(a_off[q], rsrcA, soff, base + q * NI * 1024);
     };
-    int nx_tap = 0, nx_kc = 0, nx_stage = 0;        // filter step the next issue_filter() fetches
+    int nx_grp = 0, nx_kc = 0, nx_stage = 0;        // step the next issue_filter() fetches
     auto issue_filter = [&]() {
-        const unsigned soff = (unsigned)__builtin_amdgcn_readfirstlane(
-            tap_bo[nx_tap] + (MODE == 0 ? nx_kc * 128 : nx_kc * 64 * P.b_row_pitch * 2));
-        const unsigned base = (unsigned)__builtin_amdgcn_readfirstlane(
-            (int)(lds0 + 2 * PATCHB + nx_stage * BSTAGE + fw * 1024));
 #pragma unroll
-        for (int p = 0; p < PB; ++p) dma16(b_off[p], rsrcB, soff, base + p * NI * 1024);
-        const int t1 = nx_tap + 1;
-        const bool wrap = t1 == ntaps;
-        nx_tap = __builtin_amdgcn_readfirstlane(wrap ? 0 : t1);
+        for (int tt = 0; tt < TPS; ++tt) {
+            const unsigned soff = (unsigned)__builtin_amdgcn_readfirstlane(
+                tap_bo[nx_grp * TPS + tt] + (MODE == 0 ? nx_kc * 128 : nx_kc * 64 * P.b_row_pitch * 2));
+            const unsigned base = (unsigned)__builtin_amdgcn_readfirstlane(
+                (int)(lds0 + 2 * PATCHB + nx_stage * BSTAGE + tt * BSLAB + fw * 1024));
+#pragma unroll
+            for (int p = 0; p < PB1; ++p) dma16(b_off[p], rsrcB, soff, base + p * NI * 1024);
+        }
+        const int t1 = nx_grp + 1;
+        const bool wrap = t1 == ngroups;
+        nx_grp = __builtin_amdgcn_readfirstlane(wrap ? 0 : t1);
         nx_kc = __builtin_amdgcn_readfirstlane(wrap ? nx_kc + 1 : nx_kc);
         nx_stage = __builtin_amdgcn_readfirstlane(nx_stage + 1 == SB ? 0 : nx_stage + 1);
     };
@@ -148,7 +164,7 @@ __global__ __launch_bounds__(64 * WGM * WGN) void conv_patch_kernel(IgemmParams 
 #pragma unroll
     for (int b = 0; b < FM; ++b) {
         const int ml = wm * WM + b * MF + frow;
-        pbase[b] = (ml / TW) * PW + (ml % TW);
+        pbase[b] = (ml < BM) ? (ml / TW) * PW + (ml % TW) : 0;      // padding rows read pixel 0
     }
     typedef typename std::conditional<MF == 32, float16v, float4p>::type acc_t;
     acc_t acc[FN][FM];
@@ -159,44 +175,47 @@ __global__ __launch_bounds__(64 * WGM * WGN) void conv_patch_kernel(IgemmParams 
 #pragma unroll
             for (int e = 0; e < ACCN; ++e) acc[a][b][e] = 0.f;
 
-    auto compute = [&](int kc, int tap, int stage) {
+    auto compute = [&](int kc, int grp, int stage) {
         const unsigned char* pa = smem + (kc & 1) * PATCHB;
-        const unsigned char* sb = bring + stage * BSTAGE;
-        const int po = __builtin_amdgcn_readfirstlane(tap_po[tap]);
-        int prow[FM];
 #pragma unroll
-        for (int b = 0; b < FM; ++b) prow[b] = pbase[b] + po;
+        for (int tt = 0; tt < TPS; ++tt) {
+            const unsigned char* sb = bring + stage * BSTAGE + tt * BSLAB;
+            const int po = __builtin_amdgcn_readfirstlane(tap_po[grp * TPS + tt]);
+            int prow[FM];
 #pragma unroll
-        for (int kk = 0; kk < 64 / KSTEP; ++kk) {
-            const int chunk = kk * CPK + lhi;
-            half8 fa[FM], fb[FN];
+            for (int b = 0; b < FM; ++b) prow[b] = pbase[b] + po;
 #pragma unroll
-            for (int b = 0; b < FM; ++b)
-                fa[b] = *reinterpret_cast<const half8*>(pa + prow[b] * 128 + ((chunk ^ ((prow[b] >> 1) & 7)) << 4));
+            for (int kk = 0; kk < 64 / KSTEP; ++kk) {
+                const int chunk = kk * CPK + lhi;
+                half8 fa[FM], fb[FN];
 #pragma unroll
-            for (int a = 0; a < FN; ++a) {
-                if (MODE == 0) {
-                    const int row = wn * WN + a * MF + frow;
-                    fb[a] = *reinterpret_cast<const half8*>(sb + row * 128 + ((chunk ^ ((row >> 1) & 7)) << 4));
-                } else if (MF == 32) {
-                    fb[a] = lds_frag_tr<BN>(sb, kk * 16, wn * WN + a * 32, lane);
-                } else {
-                    fb[a] = lds_frag_tr_16<BN>(sb, kk * 32, wn * WN + a * 16, lane);
+                for (int b = 0; b < FM; ++b)
+                    fa[b] = *reinterpret_cast<const half8*>(pa + prow[b] * 128 + ((chunk ^ ((prow[b] >> 1) & 7)) << 4));
+#pragma unroll
+                for (int a = 0; a < FN; ++a) {
+                    if (MODE == 0) {
+                        const int row = wn * WN + a * MF + frow;
+                        fb[a] = *reinterpret_cast<const half8*>(sb + row * 128 + ((chunk ^ ((row >> 1) & 7)) << 4));
+                    } else if (MF == 32) {
+                        fb[a] = lds_frag_tr<BN>(sb, kk * 16, wn * WN + a * 32, lane);
+                    } else {
+                        fb[a] = lds_frag_tr_16<BN>(sb, kk * 32, wn * WN + a * 16, lane);
+                    }
                 }
+#pragma unroll
+                for (int a = 0; a < FN; ++a)
+#pragma unroll
+                    for (int b = 0; b < FM; ++b) {
+                        if constexpr (MF == 32)
+                            acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_f16(fb[a], fa[b], acc[a][b], 0, 0, 0);
+                        else
+                            acc[a][b] = __builtin_amdgcn_mfma_f32_16x16x32_f16(fb[a], fa[b], acc[a][b], 0, 0, 0);
+                    }
             }
-#pragma unroll
-            for (int a = 0; a < FN; ++a)
-#pragma unroll
-                for (int b = 0; b < FM; ++b) {
-                    if constexpr (MF == 32)
-                        acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_f16(fb[a], fa[b], acc[a][b], 0, 0, 0);
-                    else
-                        acc[a][b] = __builtin_amdgcn_mfma_f32_16x16x32_f16(fb[a], fa[b], acc[a][b], 0, 0, 0);
-                }
         }
     };
 
-    // ---- pipeline: one step per (slab, tap), taps fastest ------------------------------------
+    // ---- pipeline: one step per (slab, group of TPS taps), taps fastest ------------------------------------
     if (fetcher) {
         issue_patch(0);
 #pragma unroll
@@ -222,7 +241,7 @@ __global__ __launch_bounds__(64 * WGM * WGN) void conv_patch_kernel(IgemmParams 
         }
         compute(kc, tap, stage);
         stage = (stage + 1 == SB) ? 0 : stage + 1;
-        if (++tap == ntaps) { tap = 0; ++kc; }
+        if (++tap == ngroups) { tap = 0; ++kc; }
     }
 
     // ---- epilogue ------------------------------------------------------------------------------
@@ -232,45 +251,56 @@ __global__ __launch_bounds__(64 * WGM * WGN) void conv_patch_kernel(IgemmParams 
                                [&](int r) -> long {
         const int ml = wm * WM + r;
         const int h = h0 + ml / TW, w = w0 + ml % TW;
-        if (h >= P.Hd || w >= P.Wd) return -1;
+        if (ml >= BM || h >= P.Hd || w >= P.Wd) return -1;
         return ((long)n * P.Hd + h) * P.Wd + w;
     });
 }
 
-template <int MODE, int TH, int TW, int BN, int WGM, int WGN, int SB, int MF = 32>
+template <int MODE, int TH, int TW, int BN, int WGM, int WGN, int SB, int MF = 32, int NIW = 0, int TPS = 1>
 static hipError_t launch_patch_variant(const IgemmParams& P, hipStream_t st)
 {
-    constexpr int NI = WGM * WGN / 2;
+    if ((P.R * P.S) % TPS != 0 || (P.R * P.S) / TPS < SB - 1) return hipErrorInvalidValue;
+    constexpr int NI = NIW ? NIW : WGM * WGN / 2;
     constexpr int NPL = ((TH + 2) * (TW + 2) + 8 * NI - 1) / (8 * NI);
-    constexpr size_t lds = (size_t)2 * NPL * NI * 1024 + (size_t)SB * BN * 128 + 2 * kMaxTaps * sizeof(int);
+    constexpr size_t lds = (size_t)2 * NPL * NI * 1024 + (size_t)SB * TPS * BN * 128 + 2 * kMaxTaps * sizeof(int);
     static_assert(lds <= 160 * 1024, "LDS budget");
     static bool configured = false;
     if (!configured) {
         hipError_t e = hipFuncSetAttribute(
-            reinterpret_cast<const void*>(&conv_patch_kernel<MODE, TH, TW, BN, WGM, WGN, SB, MF>),
+            reinterpret_cast<const void*>(&conv_patch_kernel<MODE, TH, TW, BN, WGM, WGN, SB, MF, NIW, TPS>),
             hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         if (e != hipSuccess) return e;
         configured = true;
     }
     const int grid = ((P.total_tiles + 63) / 64) * 64;
-    hipLaunchKernelGGL((conv_patch_kernel<MODE, TH, TW, BN, WGM, WGN, SB, MF>), dim3(grid), dim3(64 * WGM * WGN),
+    hipLaunchKernelGGL((conv_patch_kernel<MODE, TH, TW, BN, WGM, WGN, SB, MF, NIW, TPS>), dim3(grid), dim3(64 * WGM * WGN),
                        lds, st, P);
     return hipGetLastError();
 }
 
 const PatchVariant kPatchVariants[kNumPatchVariants] = {
-    {16, 16, 128, "conv_fwd_patch_16x16x128_s3", "conv_dgrad_patch_16x16x128_s3"},
-    {8, 16, 128, "conv_fwd_patch_8x16x128_s4", "conv_dgrad_patch_8x16x128_s4"},
-    {8, 16, 256, "conv_fwd_patch_8x16x256_s3", "conv_dgrad_patch_8x16x256_s3"},
-    {16, 16, 64, "conv_fwd_patch_16x16x64_s4", "conv_dgrad_patch_16x16x64_s4"},
-    {8, 32, 128, "conv_fwd_patch_8x32x128_s3", "conv_dgrad_patch_8x32x128_s3"},
-    {8, 16, 64, "conv_fwd_patch_8x16x64_s4", "conv_dgrad_patch_8x16x64_s4"},
-    {16, 16, 128, "conv_fwd_patch_16x16x128_s3_m16", "conv_dgrad_patch_16x16x128_s3_m16"},
-    {8, 16, 128, "conv_fwd_patch_8x16x128_s4_m16", "conv_dgrad_patch_8x16x128_s4_m16"},
-    {16, 16, 64, "conv_fwd_patch_16x16x64_s4_m16", "conv_dgrad_patch_16x16x64_s4_m16"},
-    {8, 32, 128, "conv_fwd_patch_8x32x128_s3_m16", "conv_dgrad_patch_8x32x128_s3_m16"},
-    {7, 16, 128, "conv_fwd_patch_7x16x128_s4_m16", "conv_dgrad_patch_7x16x128_s4_m16"},
-    {7, 16, 256, "conv_fwd_patch_7x16x256_s3_m16", "conv_dgrad_patch_7x16x256_s3_m16"},
+    {16, 16, 128, 1, 3, "conv_fwd_patch_16x16x128_s3", "conv_dgrad_patch_16x16x128_s3"},
+    {8, 16, 128, 1, 4, "conv_fwd_patch_8x16x128_s4", "conv_dgrad_patch_8x16x128_s4"},
+    {8, 16, 256, 1, 3, "conv_fwd_patch_8x16x256_s3", "conv_dgrad_patch_8x16x256_s3"},
+    {16, 16, 64, 1, 4, "conv_fwd_patch_16x16x64_s4", "conv_dgrad_patch_16x16x64_s4"},
+    {8, 32, 128, 1, 3, "conv_fwd_patch_8x32x128_s3", "conv_dgrad_patch_8x32x128_s3"},
+    {8, 16, 64, 1, 4, "conv_fwd_patch_8x16x64_s4", "conv_dgrad_patch_8x16x64_s4"},
+    {16, 16, 128, 1, 3, "conv_fwd_patch_16x16x128_s3_m16", "conv_dgrad_patch_16x16x128_s3_m16"},
+    {8, 16, 128, 1, 4, "conv_fwd_patch_8x16x128_s4_m16", "conv_dgrad_patch_8x16x128_s4_m16"},
+    {16, 16, 64, 1, 4, "conv_fwd_patch_16x16x64_s4_m16", "conv_dgrad_patch_16x16x64_s4_m16"},
+    {8, 32, 128, 1, 3, "conv_fwd_patch_8x32x128_s3_m16", "conv_dgrad_patch_8x32x128_s3_m16"},
+    {10, 14, 128, 1, 4, "conv_fwd_patch_10x14x128_6w_s4_m16", "conv_dgrad_patch_10x14x128_6w_s4_m16"},
+    {10, 14, 64, 1, 4, "conv_fwd_patch_10x14x64_6w_s4_m16", "conv_dgrad_patch_10x14x64_6w_s4_m16"},
+    {10, 14, 128, 1, 4, "conv_fwd_patch_10x14x128_12w_s4_m16", "conv_dgrad_patch_10x14x128_12w_s4_m16"},
+    {10, 14, 64, 1, 4, "conv_fwd_patch_10x14x64_6w1f_s4_m16", "conv_dgrad_patch_10x14x64_6w1f_s4_m16"},
+    {10, 14, 64, 3, 3, "conv_fwd_patch_10x14x64_6w_s3_m16_t3", "conv_dgrad_patch_10x14x64_6w_s3_m16_t3"},
+    {10, 14, 128, 3, 2, "conv_fwd_patch_10x14x128_12w_s2_m16_t3", "conv_dgrad_patch_10x14x128_12w_s2_m16_t3"},
+    {10, 14, 128, 3, 2, "conv_fwd_patch_10x14x128_6w_s2_m16_t3", "conv_dgrad_patch_10x14x128_6w_s2_m16_t3"},
+    {16, 16, 64, 3, 2, "conv_fwd_patch_16x16x64_s2_m16_t3", "conv_dgrad_patch_16x16x64_s2_m16_t3"},
+    {10, 14, 64, 3, 3, "conv_fwd_patch_10x14x64_12w_s3_m16_t3", "conv_dgrad_patch_10x14x64_12w_s3_m16_t3"},
+    {10, 14, 64, 3, 4, "conv_fwd_patch_10x14x64_6w_s4_m16_t3", "conv_dgrad_patch_10x14x64_6w_s4_m16_t3"},
+    {16, 16, 64, 3, 3, "conv_fwd_patch_16x16x64_s3_m16_t3_2f", "conv_dgrad_patch_16x16x64_s3_m16_t3_2f"},
+    {8, 16, 128, 3, 2, "conv_fwd_patch_8x16x128_s2_m16_t3", "conv_dgrad_patch_8x16x128_s2_m16_t3"},
 };
 
 #define SDCONV_PATCH_CASE(idx, TH, TW, BN, WGM, WGN, SB)                                      \
@@ -295,10 +325,30 @@ hipError_t launch_conv_patch(int variant, const IgemmParams& P, hipStream_t st)
         case 17: return launch_patch_variant<1, 16, 16, 64, 4, 2, 4, 16>(P, st);
         case 18: return launch_patch_variant<0, 8, 32, 128, 4, 2, 3, 16>(P, st);
         case 19: return launch_patch_variant<1, 8, 32, 128, 4, 2, 3, 16>(P, st);
-        case 20: return launch_patch_variant<0, 7, 16, 128, 1, 8, 4, 16>(P, st);
-        case 21: return launch_patch_variant<1, 7, 16, 128, 1, 8, 4, 16>(P, st);
-        case 22: return launch_patch_variant<0, 7, 16, 256, 1, 8, 3, 16>(P, st);
-        case 23: return launch_patch_variant<1, 7, 16, 256, 1, 8, 3, 16>(P, st);
+        case 20: return launch_patch_variant<0, 10, 14, 128, 3, 2, 4, 16, 2>(P, st);
+        case 21: return launch_patch_variant<1, 10, 14, 128, 3, 2, 4, 16, 2>(P, st);
+        case 22: return launch_patch_variant<0, 10, 14, 64, 3, 2, 4, 16, 2>(P, st);
+        case 23: return launch_patch_variant<1, 10, 14, 64, 3, 2, 4, 16, 2>(P, st);
+        case 24: return launch_patch_variant<0, 10, 14, 128, 3, 4, 4, 16, 4>(P, st);
+        case 25: return launch_patch_variant<1, 10, 14, 128, 3, 4, 4, 16, 4>(P, st);
+        case 26: return launch_patch_variant<0, 10, 14, 64, 3, 2, 4, 16, 1>(P, st);
+        case 27: return launch_patch_variant<1, 10, 14, 64, 3, 2, 4, 16, 1>(P, st);
+        case 28: return launch_patch_variant<0, 10, 14, 64, 3, 2, 3, 16, 2, 3>(P, st);
+        case 29: return launch_patch_variant<1, 10, 14, 64, 3, 2, 3, 16, 2, 3>(P, st);
+        case 30: return launch_patch_variant<0, 10, 14, 128, 3, 4, 2, 16, 4, 3>(P, st);
+        case 31: return launch_patch_variant<1, 10, 14, 128, 3, 4, 2, 16, 4, 3>(P, st);
+        case 32: return launch_patch_variant<0, 10, 14, 128, 3, 2, 2, 16, 2, 3>(P, st);
+        case 33: return launch_patch_variant<1, 10, 14, 128, 3, 2, 2, 16, 2, 3>(P, st);
+        case 34: return launch_patch_variant<0, 16, 16, 64, 4, 2, 2, 16, 0, 3>(P, st);
+        case 35: return launch_patch_variant<1, 16, 16, 64, 4, 2, 2, 16, 0, 3>(P, st);
+        case 36: return launch_patch_variant<0, 10, 14, 64, 3, 4, 3, 16, 4, 3>(P, st);
+        case 37: return launch_patch_variant<1, 10, 14, 64, 3, 4, 3, 16, 4, 3>(P, st);
+        case 38: return launch_patch_variant<0, 10, 14, 64, 3, 2, 4, 16, 2, 3>(P, st);
+        case 39: return launch_patch_variant<1, 10, 14, 64, 3, 2, 4, 16, 2, 3>(P, st);
+        case 40: return launch_patch_variant<0, 16, 16, 64, 4, 2, 3, 16, 2, 3>(P, st);
+        case 41: return launch_patch_variant<1, 16, 16, 64, 4, 2, 3, 16, 2, 3>(P, st);
+        case 42: return launch_patch_variant<0, 8, 16, 128, 2, 4, 2, 16, 0, 3>(P, st);
+        case 43: return launch_patch_variant<1, 8, 16, 128, 2, 4, 2, 16, 0, 3>(P, st);
         default: return hipErrorInvalidValue;
     }
 }

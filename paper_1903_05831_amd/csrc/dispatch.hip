@@ -96,6 +96,13 @@ static bool patch_ok(const Geom& g, bool dgrad)
            g.R * g.S >= 4;
 }
 
+static bool patch_variant_ok(const Geom& g, bool dgrad, int v)
+{
+    const PatchVariant& pv = kPatchVariants[v - 400];
+    const int taps = g.R * g.S;
+    return patch_ok(g, dgrad) && taps % pv.tps == 0 && taps / pv.tps >= pv.stages - 1;
+}
+
 static const char* igemm_name(int v, bool dgrad)
 {
     if (v >= 400) return dgrad ? kPatchVariants[v - 400].dgrad_name : kPatchVariants[v - 400].fwd_name;
@@ -105,14 +112,14 @@ static const char* igemm_name(int v, bool dgrad)
 static int pick_variant(const Geom& g, bool dgrad)
 {
     int fv = forced_variant();
-    if (fv >= 400 && fv < 400 + kNumPatchVariants && patch_ok(g, dgrad)) return fv;
+    if (fv >= 400 && fv < 400 + kNumPatchVariants && patch_variant_ok(g, dgrad, fv)) return fv;
     if (fv >= 400) fv = -1;
     if (fv >= 0 && fv < kNumIgemmVariants) return fv;
     if (fv >= 100 && fv < 100 + kNumIgemmDmaVariants) return fv;
     if (fv >= 300 && fv < 300 + kNumIgemmWsVariants) return fv;
     if (fv >= 200 && fv < 200 + kNumIgemmPersVariants && g.R * g.S * (dgrad ? g.sh * g.sw : 1) <= 1024) return fv;
     if (const TunedEntry* e = tuned_lookup(g, dgrad ? SDCONV_DGRAD : SDCONV_FWD))
-        if (e->variant < 400 || patch_ok(g, dgrad)) return e->variant;
+        if (e->variant < 400 || patch_variant_ok(g, dgrad, e->variant)) return e->variant;
     int nout = dgrad ? g.C : g.K;
     int kgemm = g.R * g.S * (dgrad ? g.K : g.C);
     int starts[kMaxClasses + 1], nc;
