@@ -83,7 +83,6 @@ static int row_tiles(const Geom& g, bool dgrad, int bm, int* starts, int* nclass
 static const IgemmVariant& igemm_variant(int v)
 {
     if (v >= 300) return kIgemmWsVariants[v - 300];
-    if (v >= 200) return kIgemmPersVariants[v - 200];
     return v >= 100 ? kIgemmDmaVariants[v - 100] : kIgemmVariants[v];
 }
 
@@ -117,7 +116,6 @@ static int pick_variant(const Geom& g, bool dgrad)
     if (fv >= 0 && fv < kNumIgemmVariants) return fv;
     if (fv >= 100 && fv < 100 + kNumIgemmDmaVariants) return fv;
     if (fv >= 300 && fv < 300 + kNumIgemmWsVariants) return fv;
-    if (fv >= 200 && fv < 200 + kNumIgemmPersVariants && g.R * g.S * (dgrad ? g.sh * g.sw : 1) <= 1024) return fv;
     if (const TunedEntry* e = tuned_lookup(g, dgrad ? SDCONV_DGRAD : SDCONV_FWD))
         if (e->variant < 400 || patch_variant_ok(g, dgrad, e->variant)) return e->variant;
     int nout = dgrad ? g.C : g.K;
@@ -234,7 +232,6 @@ static hipError_t run_igemm(const Geom& g, const Plan& p, bool dgrad, const __ha
     P.tiles_n = (P.Cd + v.bn - 1) / v.bn;
     P.total_tiles = tiles_m * P.tiles_n;
     if (p.variant >= 300) return launch_igemm_ws(p.variant - 300, P, st);
-    if (p.variant >= 200) return launch_igemm_pers(p.variant - 200, P, st);
     if (p.variant >= 100) return launch_igemm_dma(p.variant - 100, P, st);
     return launch_igemm(p.variant, P, P.total_tiles, st);
 }

@@ -33,9 +33,6 @@ extern const IgemmVariant kIgemmVariants[kNumIgemmVariants];
 constexpr int kNumIgemmDmaVariants = 12;
 extern const IgemmVariant kIgemmDmaVariants[kNumIgemmDmaVariants];
 hipError_t launch_igemm_dma(int variant, const IgemmParams& P, hipStream_t st);
-constexpr int kNumIgemmPersVariants = 10;
-extern const IgemmVariant kIgemmPersVariants[kNumIgemmPersVariants];
-hipError_t launch_igemm_pers(int variant, const IgemmParams& P, hipStream_t st);
 constexpr int kNumIgemmWsVariants = 17;
 extern const IgemmVariant kIgemmWsVariants[kNumIgemmWsVariants];
 hipError_t launch_igemm_ws(int variant, const IgemmParams& P, hipStream_t st);

@@ -83,6 +83,9 @@ def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--configs", type=str, default="1,2,3,4,5")
     ap.add_argument("--ms", type=float, default=8.0)
+    ap.add_argument("--layers", type=str, default="",
+                    help="comma-separated name fragments: tune only matching layers (a partial table, for experiments)")
+    ap.add_argument("--fwd-dgrad-only", action="store_true", help="skip the weight-gradient search")
     ap.add_argument("--out", type=str, default=os.path.join(HERE, "csrc", "tuned_table.inc"))
     ap.add_argument("--wgrad-solo", action="store_true",
                     help="pick the weight-gradient variant by its time alone instead of beside the data gradient")
@@ -100,6 +103,8 @@ def main() -> int:
         for l in workloads.CONFIGS[cfg]:
             key = (l.N, l.H, l.W, l.C, l.K, l.R, l.S, l.stride, l.pad, l.dil)
             if key in seen or l.C % 8 or l.K % 8:
+                continue
+            if args.layers and not any(f in l.name for f in args.layers.split(",")):
                 continue
             seen.add(key)
             d = sd.desc_of(l)
@@ -131,6 +136,8 @@ def main() -> int:
                 print(f"{l.name:9s} {pname:5s} best variant {v} {t*1e3:8.1f} us {l.flops/t/1e9:7.1f} TF/s   "
                       + " ".join(f"{vv}:{tt*1e3:.0f}" for tt, vv in results), flush=True)
                 lines.append(f"    {{{geom}, {pid}, {v}, 0}},  // {l.name} {pname} {t*1e3:.1f} us")
+            if args.fwd_dgrad_only:
+                continue
             # The weight gradient of a layer runs beside its data gradient on a second stream in a
             # training step: what counts is how long the pair takes, which favours variants that
             # leave compute units and bandwidth to the other kernel.
