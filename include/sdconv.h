@@ -133,6 +133,51 @@ int sgd_momentum_update(float *master_w, float *momentum_buf, const float *grad,
                         const int32_t *found_nonfinite, loss_scale_state *state, float growth,
                         float backoff, int32_t interval, void *hip_stream);
 
+/* ---- fused epilogues ------------------------------------------------------------------------
+ * Section 2.3 of the paper recalls that detectors are trained with the batch-normalisation
+ * parameters frozen: such a layer is a fixed per-channel affine map of the convolution output,
+ * followed in a residual block by the shortcut addition and the ReLU.  These two calls apply
+ * that elementwise tail to the binary32 result of the pass, before its one rounding to
+ * binary16, instead of a separate pass over the activation tensor. */
+
+/* Tail of the forward pass.  Device pointers, each optional (NULL leaves the step out):
+ *   scale, bias  binary32 [K], 16-byte aligned (frozen BN: scale = gamma / sqrt(var + eps),
+ *                bias = beta - mean * scale);
+ *   residual     binary16 [N][Ho][Wo][K] (the shortcut branch), 16-byte aligned, read only;
+ *   relu         nonzero: v <- v > 0 ? v : +0  (a NaN becomes +0). */
+typedef struct {
+    const float *scale;
+    const float *bias;
+    const void *residual;
+    int32_t relu;
+} conv2d_fwd_epilogue;
+
+/* y[n,ho,wo,k] = act( scale[k] * conv2d_fwd(x, w)[n,ho,wo,k] + bias[k] + residual[n,ho,wo,k] ),
+ * every operation in binary32 on the binary32 accumulator, one rounding to binary16 at the end.
+ * `ep` itself is a HOST pointer and must not be NULL (all members NULL / 0 gives conv2d_fwd).
+ * Workspace, alignment, ownership and error rules as conv2d_fwd; y must not overlap residual. */
+int conv2d_fwd_fused(const conv2d_desc *desc, const void *x, const void *w,
+                     const conv2d_fwd_epilogue *ep, void *y, void *workspace,
+                     size_t workspace_bytes, void *hip_stream);
+
+/* Tail of the data gradient: the chain rule through a = relu(scale * z + bias), the activation
+ * that feeds this convolution (dx is then dL/dz of the layer before).  Device pointers, each
+ * optional:
+ *   scale      binary32 [C], 16-byte aligned (the affine map's factor; bias does not enter);
+ *   relu_mask  binary16 [N][H][W][C], 16-byte aligned: the activation a itself (the x of the
+ *              forward pass); the gradient passes where relu_mask > 0, strictly. */
+typedef struct {
+    const float *scale;
+    const void *relu_mask;
+} conv2d_dgrad_epilogue;
+
+/* dx[n,h,w,c] = relu_mask[n,h,w,c] > 0 ? scale[c] * conv2d_dgrad(dy, w)[n,h,w,c] : +0,
+ * in binary32 on the binary32 accumulator, one rounding to binary16.  `ep` is a HOST pointer,
+ * not NULL.  Otherwise as conv2d_dgrad; dx must not overlap relu_mask. */
+int conv2d_dgrad_fused(const conv2d_desc *desc, const void *dy, const void *w,
+                       const conv2d_dgrad_epilogue *ep, void *dx, void *workspace,
+                       size_t workspace_bytes, void *hip_stream);
+
 /* Static, human-readable text for a status code. */
 const char *sdconv_status_string(int status);
 

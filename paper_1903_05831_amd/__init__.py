@@ -22,6 +22,7 @@ EXPORTS = (
     "conv2d_out_shape", "conv2d_workspace_bytes", "conv2d_fwd", "conv2d_dgrad", "conv2d_wgrad",
     "grad_unscale_check", "sdconv_status_string", "sdconv_last_hip_error", "sdconv_kernel_name",
     "sdconv_mfma_ceiling", "grad_unscale_check_dynamic", "sgd_momentum_update",
+    "conv2d_fwd_fused", "conv2d_dgrad_fused",
 )
 
 
@@ -29,6 +30,15 @@ class conv2d_desc(ctypes.Structure):
     _fields_ = [(n, ctypes.c_int32) for n in (
         "N", "H", "W", "C", "K", "R", "S",
         "stride_h", "stride_w", "pad_h", "pad_w", "dil_h", "dil_w")]
+
+
+class conv2d_fwd_epilogue(ctypes.Structure):
+    _fields_ = [("scale", ctypes.c_void_p), ("bias", ctypes.c_void_p), ("residual", ctypes.c_void_p),
+                ("relu", ctypes.c_int32)]
+
+
+class conv2d_dgrad_epilogue(ctypes.Structure):
+    _fields_ = [("scale", ctypes.c_void_p), ("relu_mask", ctypes.c_void_p)]
 
 
 class SdconvError(RuntimeError):
@@ -71,6 +81,10 @@ def lib() -> ctypes.CDLL:
         f32 = ctypes.c_float
         L.sgd_momentum_update.argtypes = [vp, vp, vp, vp, sz, f32, f32, f32, vp, vp, f32, f32, ctypes.c_int32, vp]
         L.sgd_momentum_update.restype = ctypes.c_int
+        L.conv2d_fwd_fused.argtypes = [dp, vp, vp, ctypes.POINTER(conv2d_fwd_epilogue), vp, vp, sz, vp]
+        L.conv2d_fwd_fused.restype = ctypes.c_int
+        L.conv2d_dgrad_fused.argtypes = [dp, vp, vp, ctypes.POINTER(conv2d_dgrad_epilogue), vp, vp, sz, vp]
+        L.conv2d_dgrad_fused.restype = ctypes.c_int
         L.sdconv_mfma_ceiling.argtypes = [vp, ctypes.c_int, ctypes.c_int, vp]
         L.sdconv_mfma_ceiling.restype = ctypes.c_int
         _lib = L
@@ -141,6 +155,26 @@ def conv2d_fwd(desc, x, w, y, workspace=None, stream: int = 0) -> None:
 
 def conv2d_dgrad(desc, dy, w, dx, workspace=None, stream: int = 0) -> None:
     _call("conv2d_dgrad", desc, dy, w, dx, workspace, stream)
+
+
+def conv2d_fwd_fused(desc, x, w, y, workspace=None, stream: int = 0, *, scale=None, bias=None, residual=None,
+                     relu: bool = False) -> None:
+    """y = act(scale[k] * conv(x, w) + bias[k] + residual); scale, bias: fp32 [K] device tensors."""
+    ep = conv2d_fwd_epilogue(_ptr(scale) or None, _ptr(bias) or None, _ptr(residual) or None, 1 if relu else 0)
+    wp, wb = _ws(workspace)
+    rc = lib().conv2d_fwd_fused(ctypes.byref(desc), _ptr(x), _ptr(w), ctypes.byref(ep), _ptr(y), wp, wb, stream or 0)
+    if rc:
+        raise SdconvError(rc, "conv2d_fwd_fused")
+
+
+def conv2d_dgrad_fused(desc, dy, w, dx, workspace=None, stream: int = 0, *, scale=None, relu_mask=None) -> None:
+    """dx = relu_mask > 0 ? scale[c] * dgrad(dy, w) : 0; scale: fp32 [C], relu_mask: fp16 like dx."""
+    ep = conv2d_dgrad_epilogue(_ptr(scale) or None, _ptr(relu_mask) or None)
+    wp, wb = _ws(workspace)
+    rc = lib().conv2d_dgrad_fused(ctypes.byref(desc), _ptr(dy), _ptr(w), ctypes.byref(ep), _ptr(dx), wp, wb,
+                                  stream or 0)
+    if rc:
+        raise SdconvError(rc, "conv2d_dgrad_fused")
 
 
 def conv2d_wgrad(desc, x, dy, dw, workspace=None, stream: int = 0) -> None:

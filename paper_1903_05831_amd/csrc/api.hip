@@ -98,6 +98,40 @@ extern "C" __attribute__((visibility("default"))) int conv2d_dgrad(const conv2d_
                                 (hipStream_t)hip_stream));
 }
 
+extern "C" __attribute__((visibility("default"))) int conv2d_fwd_fused(const conv2d_desc* desc, const void* x, const void* w,
+                                                                       const conv2d_fwd_epilogue* ep, void* y,
+                                                                       void* workspace, size_t workspace_bytes,
+                                                                       void* hip_stream)
+{
+    int Ho, Wo;
+    if (!desc_shape(desc, &Ho, &Wo) || !ep) return SDCONV_EINVAL;
+    if (!aligned16(ep->scale) || !aligned16(ep->bias) || !aligned16(ep->residual)) return SDCONV_EINVAL;
+    Geom g = make_geom(*desc, Ho, Wo);
+    Plan p = plan_fwd(g);
+    int rc = check_common(desc, x, w, y, workspace, workspace_bytes, p.workspace_bytes, &Ho, &Wo);
+    if (rc) return rc;
+    Epilogue E{ep->scale, ep->bias, static_cast<const __half*>(ep->residual), nullptr, ep->relu ? 1 : 0};
+    return hip_status(run_fwd(g, p, (const __half*)x, (const __half*)w, (__half*)y, workspace,
+                              (hipStream_t)hip_stream, E));
+}
+
+extern "C" __attribute__((visibility("default"))) int conv2d_dgrad_fused(const conv2d_desc* desc, const void* dy, const void* w,
+                                                                         const conv2d_dgrad_epilogue* ep, void* dx,
+                                                                         void* workspace, size_t workspace_bytes,
+                                                                         void* hip_stream)
+{
+    int Ho, Wo;
+    if (!desc_shape(desc, &Ho, &Wo) || !ep) return SDCONV_EINVAL;
+    if (!aligned16(ep->scale) || !aligned16(ep->relu_mask)) return SDCONV_EINVAL;
+    Geom g = make_geom(*desc, Ho, Wo);
+    Plan p = plan_dgrad(g);
+    int rc = check_common(desc, dy, w, dx, workspace, workspace_bytes, p.workspace_bytes, &Ho, &Wo);
+    if (rc) return rc;
+    Epilogue E{ep->scale, nullptr, nullptr, static_cast<const __half*>(ep->relu_mask), 0};
+    return hip_status(run_dgrad(g, p, (const __half*)dy, (const __half*)w, (__half*)dx, workspace,
+                                (hipStream_t)hip_stream, E));
+}
+
 extern "C" __attribute__((visibility("default"))) int conv2d_wgrad(const conv2d_desc* desc, const void* x, const void* dy, float* dw,
                             void* workspace, size_t workspace_bytes, void* hip_stream)
 {

@@ -25,6 +25,32 @@ inline Geom make_geom(const conv2d_desc& d, int Ho, int Wo)
     return g;
 }
 
+// Elementwise tail applied to the fp32 result of a forward or data-gradient pass before its one
+// rounding to binary16 (a frozen batch normalisation is the affine part, section 2.3 of the
+// paper; shortcut and ReLU are what follows it in a residual block).  c is the destination
+// channel, i the flat NHWC index of the destination element:
+//   v = acc;  v *= scale[c];  v += bias[c];  v += residual[i];  relu: v = v > 0 ? v : 0;
+//   mask: v = mask[i] > 0 ? v : 0          (null pointers / relu == 0 leave a step out)
+struct Epilogue {
+    const float* scale;
+    const float* bias;
+    const __half* residual;
+    const __half* mask;
+    int relu;
+    __host__ __device__ bool any() const { return scale || bias || residual || mask || relu; }
+};
+inline Epilogue no_epilogue() { return Epilogue{nullptr, nullptr, nullptr, nullptr, 0}; }
+
+__device__ __forceinline__ float epilogue_apply(const Epilogue& E, float v, int c, long i)
+{
+    if (E.scale) v *= E.scale[c];
+    if (E.bias) v += E.bias[c];
+    if (E.residual) v += __half2float(E.residual[i]);
+    if (E.relu) v = v > 0.f ? v : 0.f;
+    if (E.mask) v = __half2float(E.mask[i]) > 0.f ? v : 0.f;
+    return v;
+}
+
 // What the dispatcher decided for one (geometry, pass).
 enum Route { ROUTE_DIRECT = 0, ROUTE_IGEMM = 1, ROUTE_THIN = 2 };
 struct Plan {
@@ -37,13 +63,17 @@ struct Plan {
 Plan plan_fwd(const Geom& g);
 Plan plan_dgrad(const Geom& g);
 Plan plan_wgrad(const Geom& g);
-hipError_t run_fwd(const Geom& g, const Plan& p, const __half* x, const __half* w, __half* y, void* ws, hipStream_t st);
-hipError_t run_dgrad(const Geom& g, const Plan& p, const __half* dy, const __half* w, __half* dx, void* ws, hipStream_t st);
+hipError_t run_fwd(const Geom& g, const Plan& p, const __half* x, const __half* w, __half* y, void* ws, hipStream_t st,
+                   const Epilogue& ep = no_epilogue());
+hipError_t run_dgrad(const Geom& g, const Plan& p, const __half* dy, const __half* w, __half* dx, void* ws, hipStream_t st,
+                     const Epilogue& ep = no_epilogue());
 hipError_t run_wgrad(const Geom& g, const Plan& p, const __half* x, const __half* dy, float* dw, void* ws, hipStream_t st);
 
 // Launchers return hipGetLastError() of their launches.  All work goes to `st`.
-hipError_t launch_direct_fwd(const Geom& g, const __half* x, const __half* w, __half* y, hipStream_t st);
-hipError_t launch_direct_dgrad(const Geom& g, const __half* dy, const __half* w, __half* dx, hipStream_t st);
+hipError_t launch_direct_fwd(const Geom& g, const __half* x, const __half* w, __half* y, hipStream_t st,
+                             const Epilogue& ep = no_epilogue());
+hipError_t launch_direct_dgrad(const Geom& g, const __half* dy, const __half* w, __half* dx, hipStream_t st,
+                               const Epilogue& ep = no_epilogue());
 hipError_t launch_direct_wgrad(const Geom& g, const __half* x, const __half* dy, float* dw, hipStream_t st);
 hipError_t launch_unscale_check(float* grad, size_t n, float inv_scale, const float* scale_on_device,
                                 int32_t* flag, hipStream_t st);

@@ -245,8 +245,9 @@ __global__ __launch_bounds__(64 * WGM * WGN) void conv_patch_kernel(IgemmParams 
     }
 
     // ---- epilogue ------------------------------------------------------------------------------
-    static_assert(NW * epilogue_strip_bytes<WN, MF>() <= 2 * PATCHB, "epilogue strips fit in the patch buffers");
-    __builtin_amdgcn_s_barrier();                   // everybody is done reading the last patch
+    static_assert(NW * epilogue_strip_bytes<WN, MF>() <= 2 * PATCHB + SB * TPS * BN * 128,
+                  "epilogue strips fit in the patch buffers and the filter ring");
+    __builtin_amdgcn_s_barrier();                   // everybody is done reading the last patch and filter stage
     store_rows_via_lds<FM, FN, MF>(acc, smem + wave * epilogue_strip_bytes<WN, MF>(), lane, n0 + wn * WN, P,
                                [&](int r) -> long {
         const int ml = wm * WM + r;

@@ -1,13 +1,14 @@
 // Direct (one result per thread / per block) convolution kernels.  They accept every
 // valid descriptor and are the route for channel counts the MFMA kernels do not tile
-// (C or K not a multiple of 8).  fp16 inputs, fp32 accumulation, one rounding on store.
+// (C or K not a multiple of 8).  fp16 inputs, fp32 accumulation, the optional elementwise
+// tail in fp32, one rounding on store.
 #include "common.h"
 
 namespace sdconv {
 
 __global__ __launch_bounds__(256) void direct_fwd_kernel(Geom g, const __half* __restrict__ x,
                                                          const __half* __restrict__ w,
-                                                         __half* __restrict__ y, long total)
+                                                         __half* __restrict__ y, long total, Epilogue E)
 {
     long i = (long)blockIdx.x * blockDim.x + threadIdx.x;
     if (i >= total) return;
@@ -28,12 +29,12 @@ __global__ __launch_bounds__(256) void direct_fwd_kernel(Geom g, const __half* _
             for (int c = 0; c < g.C; ++c) acc += __half2float(xp[c]) * __half2float(wp[c]);
         }
     }
-    y[i] = __float2half_rn(acc);
+    y[i] = __float2half_rn(epilogue_apply(E, acc, k, i));
 }
 
 __global__ __launch_bounds__(256) void direct_dgrad_kernel(Geom g, const __half* __restrict__ dy,
                                                            const __half* __restrict__ w,
-                                                           __half* __restrict__ dx, long total)
+                                                           __half* __restrict__ dx, long total, Epilogue E)
 {
     long i = (long)blockIdx.x * blockDim.x + threadIdx.x;
     if (i >= total) return;
@@ -59,7 +60,7 @@ __global__ __launch_bounds__(256) void direct_dgrad_kernel(Geom g, const __half*
             for (int k = 0; k < g.K; ++k) acc += __half2float(gp[k]) * __half2float(wp[k * wstride]);
         }
     }
-    dx[i] = __float2half_rn(acc);
+    dx[i] = __float2half_rn(epilogue_apply(E, acc, c, i));
 }
 
 // One workgroup per dw element: threads stride over output pixels, then a fixed-order
@@ -99,17 +100,19 @@ __global__ __launch_bounds__(256) void direct_wgrad_kernel(Geom g, const __half*
 
 static inline unsigned blocks_for(long total) { return (unsigned)((total + 255) / 256); }
 
-hipError_t launch_direct_fwd(const Geom& g, const __half* x, const __half* w, __half* y, hipStream_t st)
+hipError_t launch_direct_fwd(const Geom& g, const __half* x, const __half* w, __half* y, hipStream_t st,
+                             const Epilogue& ep)
 {
     long total = (long)g.N * g.Ho * g.Wo * g.K;
-    hipLaunchKernelGGL(direct_fwd_kernel, dim3(blocks_for(total)), dim3(256), 0, st, g, x, w, y, total);
+    hipLaunchKernelGGL(direct_fwd_kernel, dim3(blocks_for(total)), dim3(256), 0, st, g, x, w, y, total, ep);
     return hipGetLastError();
 }
 
-hipError_t launch_direct_dgrad(const Geom& g, const __half* dy, const __half* w, __half* dx, hipStream_t st)
+hipError_t launch_direct_dgrad(const Geom& g, const __half* dy, const __half* w, __half* dx, hipStream_t st,
+                               const Epilogue& ep)
 {
     long total = (long)g.N * g.H * g.W * g.C;
-    hipLaunchKernelGGL(direct_dgrad_kernel, dim3(blocks_for(total)), dim3(256), 0, st, g, dy, w, dx, total);
+    hipLaunchKernelGGL(direct_dgrad_kernel, dim3(blocks_for(total)), dim3(256), 0, st, g, dy, w, dx, total, ep);
     return hipGetLastError();
 }
 

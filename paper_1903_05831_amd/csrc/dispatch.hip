@@ -200,9 +200,10 @@ Plan plan_wgrad(const Geom& g)
 }
 
 static hipError_t run_igemm(const Geom& g, const Plan& p, bool dgrad, const __half* A, const __half* B,
-                            __half* D, hipStream_t st)
+                            __half* D, hipStream_t st, const Epilogue& ep)
 {
     IgemmParams P;
+    P.ep = ep;
     P.A = A; P.B = B; P.D = D;
     P.NB = g.N;
     if (!dgrad) { P.Hs = g.H; P.Ws = g.W; P.Cs = g.C; P.Hd = g.Ho; P.Wd = g.Wo; P.Cd = g.K; }
@@ -236,23 +237,25 @@ static hipError_t run_igemm(const Geom& g, const Plan& p, bool dgrad, const __ha
     return launch_igemm(p.variant, P, P.total_tiles, st);
 }
 
-hipError_t run_fwd(const Geom& g, const Plan& p, const __half* x, const __half* w, __half* y, void* ws, hipStream_t st)
+hipError_t run_fwd(const Geom& g, const Plan& p, const __half* x, const __half* w, __half* y, void* ws, hipStream_t st,
+                   const Epilogue& ep)
 {
-    if (p.route == ROUTE_DIRECT) return launch_direct_fwd(g, x, w, y, st);
-    if (p.route == ROUTE_THIN) return launch_thin_fwd(g, x, w, y, ws, st);
-    return run_igemm(g, p, false, x, w, y, st);
+    if (p.route == ROUTE_DIRECT) return launch_direct_fwd(g, x, w, y, st, ep);
+    if (p.route == ROUTE_THIN) return launch_thin_fwd(g, x, w, y, ws, st, ep);
+    return run_igemm(g, p, false, x, w, y, st, ep);
 }
 
-hipError_t run_dgrad(const Geom& g, const Plan& p, const __half* dy, const __half* w, __half* dx, void* ws, hipStream_t st)
+hipError_t run_dgrad(const Geom& g, const Plan& p, const __half* dy, const __half* w, __half* dx, void* ws, hipStream_t st,
+                     const Epilogue& ep)
 {
-    if (p.route == ROUTE_DIRECT) return launch_direct_dgrad(g, dy, w, dx, st);
-    if (p.route == ROUTE_THIN && p.variant == 1) return launch_thin_dgrad_mfma(g, dy, w, dx, ws, st);
-    if (p.route == ROUTE_IGEMM && p.variant >= 300) return run_igemm(g, p, true, dy, w, dx, st);
+    if (p.route == ROUTE_DIRECT) return launch_direct_dgrad(g, dy, w, dx, st, ep);
+    if (p.route == ROUTE_THIN && p.variant == 1) return launch_thin_dgrad_mfma(g, dy, w, dx, ws, st, ep);
+    if (p.route == ROUTE_IGEMM && p.variant >= 300) return run_igemm(g, p, true, dy, w, dx, st, ep);
     __half* wT = static_cast<__half*>(ws);
     hipError_t e = launch_filter_transpose(w, wT, g.K, g.R * g.S, g.C, st);
     if (e != hipSuccess) return e;
-    if (p.route == ROUTE_THIN) return launch_thin_dgrad(g, dy, wT, dx, st);
-    return run_igemm(g, p, true, dy, wT, dx, st);
+    if (p.route == ROUTE_THIN) return launch_thin_dgrad(g, dy, wT, dx, st, ep);
+    return run_igemm(g, p, true, dy, wT, dx, st, ep);
 }
 
 hipError_t run_wgrad(const Geom& g, const Plan& p, const __half* x, const __half* dy, float* dw, void* ws, hipStream_t st)

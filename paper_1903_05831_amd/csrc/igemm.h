@@ -24,6 +24,7 @@ struct IgemmParams {
     int b_row_pitch;   // R*S*Cs
     int class_tile_start[kMaxClasses + 1];   // first row-tile of each class, then the total
     int tiles_h, tiles_w;   // spatial tiles per image (patch kernels only)
+    Epilogue ep;            // elementwise tail before the rounding to binary16 (all null: none)
 };
 
 struct IgemmVariant { int bm, bn; const char* fwd_name; const char* dgrad_name; };

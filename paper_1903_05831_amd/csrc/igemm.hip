@@ -224,10 +224,10 @@ __global__ __launch_bounds__(kThreads) void igemm_kernel(IgemmParams P)
                 int col = n0 + wn * WN + a * 32 + 8 * q + 4 * lhi;
                 if (col < P.Cd) {
                     half4 h;
-                    h[0] = (_Float16)acc[a][b][4 * q + 0];
-                    h[1] = (_Float16)acc[a][b][4 * q + 1];
-                    h[2] = (_Float16)acc[a][b][4 * q + 2];
-                    h[3] = (_Float16)acc[a][b][4 * q + 3];
+                    const long o = (drow - P.D) + col;
+#pragma unroll
+                    for (int e = 0; e < 4; ++e)
+                        h[e] = (_Float16)epilogue_apply(P.ep, acc[a][b][4 * q + e], col + e, o + e);
                     *reinterpret_cast<half4*>(drow + col) = h;
                 }
             }

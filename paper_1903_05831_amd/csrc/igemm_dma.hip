@@ -32,6 +32,14 @@ typedef _Float16 half4 __attribute__((ext_vector_type(4)));
 typedef float float16v __attribute__((ext_vector_type(16)));
 
 // BK = contraction halves per stage (64 or 32): a tile row is BK*2 bytes = CPR 16-byte chunks.
+// Dynamic LDS of a variant: the ring and the tap tables, or the epilogue strips if those need more.
+template <int BM, int BN, int WGM, int WGN, int S, int BK> constexpr size_t dma_lds_bytes()
+{
+    constexpr size_t loop = (size_t)S * (BM + BN) * BK * 2 + (4 * kMaxTaps + 4) * sizeof(int);
+    constexpr size_t strips = (size_t)WGM * WGN * epilogue_strip_bytes<BN / WGN>();
+    return loop > strips ? loop : strips;
+}
+
 template <int MODE, int BM, int BN, int WGM, int WGN, int S, int BK>
 __global__ __launch_bounds__(64 * WGM * WGN) void igemm_dma_kernel(IgemmParams P)
 {
@@ -224,7 +232,8 @@ __global__ __launch_bounds__(64 * WGM * WGN) void igemm_dma_kernel(IgemmParams P
     }
 
     // ---- epilogue: through a per-wave LDS strip into 16-byte NHWC stores --------------------
-    static_assert(NW * epilogue_strip_bytes<WN>() <= S * STAGE, "epilogue strips fit in the ring");
+    // (the strips may run over the tap tables behind the ring: those are dead by now)
+    static_assert(NW * epilogue_strip_bytes<WN>() <= dma_lds_bytes<BM, BN, WGM, WGN, S, BK>(), "epilogue strips fit in LDS");
     __builtin_amdgcn_s_barrier();                   // everybody is done reading the last stage
     store_tile_via_lds<FM, FN>(acc, smem + wave * epilogue_strip_bytes<WN>(), lane, m0 + wm * WM, n0 + wn * WN,
                                Mcls, P, Hi, Wj, eh, ew, ca, cb);
@@ -233,7 +242,7 @@ __global__ __launch_bounds__(64 * WGM * WGN) void igemm_dma_kernel(IgemmParams P
 template <int MODE, int BM, int BN, int WGM, int WGN, int S, int BK>
 static hipError_t launch_dma_variant(const IgemmParams& P, hipStream_t st)
 {
-    constexpr size_t lds = (size_t)S * (BM + BN) * BK * 2 + (4 * kMaxTaps + 4) * sizeof(int);
+    constexpr size_t lds = dma_lds_bytes<BM, BN, WGM, WGN, S, BK>();
     static_assert(lds <= 160 * 1024, "LDS budget");
     static bool configured = false;
     if (!configured) {

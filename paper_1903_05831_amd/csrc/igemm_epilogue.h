@@ -8,17 +8,35 @@
 // 32 rows x WN columns in a private LDS strip (row pitch padded by 16 bytes against bank
 // conflicts) and reads it back with consecutive lanes on consecutive 16-byte chunks of a row,
 // so every store instruction writes whole 64/128-byte row segments.
+//
 #pragma once
 #include "common.h"
 #include "igemm.h"
 
 namespace sdconv {
 
-template <int WN, int MF = 32> constexpr int epilogue_strip_bytes() { return MF * (WN * 2 + 16); }
+// With an elementwise tail (P.ep) the strip holds the fp32 accumulators instead, and scale,
+// bias, shortcut, ReLU and mask are applied after the read-back, where a lane owns 8 consecutive
+// channels of one pixel: the shortcut / mask tensors are read with the same 16-byte row-
+// contiguous accesses as the result is written, and the result is rounded to binary16 once.
+//
+// The strip is sized for the fp32 form (the plain form uses the first half of each row).
+template <int WN, int MF = 32> constexpr int epilogue_strip_bytes() { return MF * (WN * 4 + 16); }
 
-// acc[a][b]: block (rows b*32.., columns a*32..) of the wave's WM x WN sub-tile.
-// strip: this wave's private LDS area of epilogue_strip_bytes<WN>() bytes; the caller has made
-// sure (workgroup barrier) that nobody still reads what the strip overwrites.
+// Lanes of one wave hand data to each other through the strip.  The hardware completes the LDS
+// operations of a wave in order, but to the compiler the lanes are independent threads: without
+// this it may move the writes of lanes that skip the read-back (more lanes than strip chunks)
+// past the reads of the others.  No instruction is emitted for it.
+__device__ __forceinline__ void strip_handover()
+{
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
+
+// acc[a][b]: block (rows b*MF.., columns a*MF..) of the wave's WM x WN sub-tile.
+// strip: this wave's private LDS area of epilogue_strip_bytes<WN, MF>() bytes; the caller has
+// made sure (workgroup barrier) that nobody still reads what the strip overwrites.
 // pix_of(r): destination pixel index (n*Hd + h)*Wd + w of row r of the wave's sub-tile, or a
 // negative value for rows that have no destination.  col_base: first destination channel.
 // MF = 32: accumulators of v_mfma_f32_32x32x16_f16 blocks (16 floats per lane: row lane%32,
@@ -30,38 +48,115 @@ __device__ __forceinline__ void store_rows_via_lds(Acc (&acc)[FN][FM], unsigned 
 {
     typedef _Float16 h4 __attribute__((ext_vector_type(4)));
     typedef _Float16 h8 __attribute__((ext_vector_type(8)));
+    typedef float f4 __attribute__((ext_vector_type(4)));
     constexpr int WN = FN * MF;
-    constexpr int CW = WN / 8;                      // 16-byte chunks per strip row
+    constexpr int CW = WN / 8;                      // 8-channel chunks per strip row
     constexpr int RPI = 64 / CW;                    // strip rows one store instruction covers
-    constexpr int PITCH = WN * 2 + 16;
     static_assert(MF % RPI == 0 || RPI % MF == 0, "strip rows per instruction");
     const int lrow = lane & (MF - 1), lhi = lane / MF;
     const int srow = lane / CW, schunk = lane % CW;
+    const int col = col_base + schunk * 8;          // first of this lane's 8 destination channels
+
+    if (!P.ep.any()) {
+        constexpr int PITCH = WN * 2 + 16;
+#pragma unroll
+        for (int b = 0; b < FM; ++b) {
+#pragma unroll
+            for (int a = 0; a < FN; ++a) {
+#pragma unroll
+                for (int q = 0; q < (MF == 32 ? 4 : 1); ++q) {
+                    h4 h;
+                    h[0] = (_Float16)acc[a][b][4 * q + 0];
+                    h[1] = (_Float16)acc[a][b][4 * q + 1];
+                    h[2] = (_Float16)acc[a][b][4 * q + 2];
+                    h[3] = (_Float16)acc[a][b][4 * q + 3];
+                    const int scol = (MF == 32) ? a * 32 + 8 * q + 4 * lhi : a * 16 + 4 * lhi;
+                    *reinterpret_cast<h4*>(strip + lrow * PITCH + scol * 2) = h;
+                }
+            }
+            // the strip is private to the wave, and LDS operations of one wave complete in order
+            strip_handover();
+#pragma unroll
+            for (int j = 0; j < (MF + RPI - 1) / RPI; ++j) {
+                const int r = j * RPI + srow;
+                if (RPI <= MF || r < MF) {              // (there may be more lanes than strip chunks)
+                    h8 v = *reinterpret_cast<const h8*>(strip + r * PITCH + schunk * 16);
+                    const long pix = pix_of(b * MF + r);
+                    if (pix >= 0 && col < P.Cd) *reinterpret_cast<h8*>(P.D + pix * P.Cd + col) = v;
+                }
+            }
+            strip_handover();
+        }
+        return;
+    }
+
+    // ---- with the elementwise tail: fp32 strip ------------------------------------------------
+    constexpr int PITCH = WN * 4 + 16;
+    const Epilogue& E = P.ep;
+    const bool live = col < P.Cd;                   // Cd is a multiple of 8 on this route: all 8 or none
+    f4 sc0 = {1.f, 1.f, 1.f, 1.f}, sc1 = sc0, bi0 = {0.f, 0.f, 0.f, 0.f}, bi1 = bi0;
+    if (live && E.scale) {
+        sc0 = *reinterpret_cast<const f4*>(E.scale + col);
+        sc1 = *reinterpret_cast<const f4*>(E.scale + col + 4);
+    }
+    if (live && E.bias) {
+        bi0 = *reinterpret_cast<const f4*>(E.bias + col);
+        bi1 = *reinterpret_cast<const f4*>(E.bias + col + 4);
+    }
 #pragma unroll
     for (int b = 0; b < FM; ++b) {
 #pragma unroll
         for (int a = 0; a < FN; ++a) {
 #pragma unroll
             for (int q = 0; q < (MF == 32 ? 4 : 1); ++q) {
-                h4 h;
-                h[0] = (_Float16)acc[a][b][4 * q + 0];
-                h[1] = (_Float16)acc[a][b][4 * q + 1];
-                h[2] = (_Float16)acc[a][b][4 * q + 2];
-                h[3] = (_Float16)acc[a][b][4 * q + 3];
-                const int col = (MF == 32) ? a * 32 + 8 * q + 4 * lhi : a * 16 + 4 * lhi;
-                *reinterpret_cast<h4*>(strip + lrow * PITCH + col * 2) = h;
+                f4 f;
+                f[0] = acc[a][b][4 * q + 0];
+                f[1] = acc[a][b][4 * q + 1];
+                f[2] = acc[a][b][4 * q + 2];
+                f[3] = acc[a][b][4 * q + 3];
+                const int scol = (MF == 32) ? a * 32 + 8 * q + 4 * lhi : a * 16 + 4 * lhi;
+                *reinterpret_cast<f4*>(strip + lrow * PITCH + scol * 4) = f;
             }
         }
-        // the strip is private to the wave, and LDS operations of one wave complete in order
+        strip_handover();
 #pragma unroll
         for (int j = 0; j < (MF + RPI - 1) / RPI; ++j) {
             const int r = j * RPI + srow;
-            if (RPI > MF && r >= MF) continue;      // more lanes than strip chunks
-            h8 v = *reinterpret_cast<const h8*>(strip + r * PITCH + schunk * 16);
-            const int col = col_base + schunk * 8;
-            const long pix = pix_of(b * MF + r);
-            if (pix >= 0 && col < P.Cd) *reinterpret_cast<h8*>(P.D + pix * P.Cd + col) = v;
+            const bool mine = RPI <= MF || r < MF;      // (there may be more lanes than strip chunks)
+            f4 v0 = {0.f, 0.f, 0.f, 0.f}, v1 = v0;
+            if (mine) {
+                v0 = *reinterpret_cast<const f4*>(strip + r * PITCH + schunk * 32);
+                v1 = *reinterpret_cast<const f4*>(strip + r * PITCH + schunk * 32 + 16);
+            }
+            const long pix = mine ? pix_of(b * MF + r) : -1;
+            if (pix < 0 || !live) continue;
+            const long i = pix * P.Cd + col;
+            float v[8];
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                v[e] = v0[e] * sc0[e] + bi0[e];
+                v[4 + e] = v1[e] * sc1[e] + bi1[e];
+            }
+            if (E.residual) {
+                h8 rr = *reinterpret_cast<const h8*>(reinterpret_cast<const _Float16*>(E.residual) + i);
+#pragma unroll
+                for (int e = 0; e < 8; ++e) v[e] += (float)rr[e];
+            }
+            if (E.relu) {
+#pragma unroll
+                for (int e = 0; e < 8; ++e) v[e] = v[e] > 0.f ? v[e] : 0.f;
+            }
+            if (E.mask) {
+                h8 mm = *reinterpret_cast<const h8*>(reinterpret_cast<const _Float16*>(E.mask) + i);
+#pragma unroll
+                for (int e = 0; e < 8; ++e) v[e] = (float)mm[e] > 0.f ? v[e] : 0.f;
+            }
+            h8 o;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) o[e] = (_Float16)v[e];
+            *reinterpret_cast<h8*>(P.D + i) = o;
         }
+        strip_handover();
     }
 }
 

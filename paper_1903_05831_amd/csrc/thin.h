@@ -14,6 +14,7 @@ struct ThinParams {
     int sh, sw, ph, pw, Ho, Wo;
     int tiles_h, tiles_w, ntiles;   // 8x32 output tiles
     int PH, PW;                     // LDS patch extent in padded pixels
+    Epilogue ep;                    // forward: elementwise tail before the rounding
 };
 
 struct ThinDgradParams {
@@ -24,6 +25,7 @@ struct ThinDgradParams {
     int sh, sw, ph, pw, dh, dw, Ho, Wo;
     int nclasses;
     int class_block_start[17];
+    Epilogue ep;
 };
 
 struct ThinDgradMfmaParams {
@@ -34,19 +36,22 @@ struct ThinDgradMfmaParams {
     int sh, sw, ph, pw, dh, dw, Ho, Wo;
     int ohmin, owmin, RP, SP;   // window of dy displacements over all parity classes
     int tiles_i, tiles_j;       // 8x32 macro-pixel tiles
+    Epilogue ep;
 };
 
 bool thin_dgrad_mfma_supported(const Geom& g);
 size_t thin_dgrad_mfma_workspace_bytes(const Geom& g);
 hipError_t launch_thin_dgrad_mfma(const Geom& g, const __half* dy, const __half* w, __half* dx, void* ws,
-                                  hipStream_t st);
+                                  hipStream_t st, const Epilogue& ep = no_epilogue());
 
 bool thin_supported(const Geom& g);
 size_t thin_dgrad_lds_bytes(const Geom& g);
-hipError_t launch_thin_dgrad(const Geom& g, const __half* dy, const __half* wT, __half* dx, hipStream_t st);
+hipError_t launch_thin_dgrad(const Geom& g, const __half* dy, const __half* wT, __half* dx, hipStream_t st,
+                             const Epilogue& ep = no_epilogue());
 size_t thin_packed_filter_bytes(const Geom& g);
 size_t thin_wgrad_partial_bytes(const Geom& g);
-hipError_t launch_thin_fwd(const Geom& g, const __half* x, const __half* w, __half* y, void* ws, hipStream_t st);
+hipError_t launch_thin_fwd(const Geom& g, const __half* x, const __half* w, __half* y, void* ws, hipStream_t st,
+                           const Epilogue& ep = no_epilogue());
 hipError_t launch_thin_wgrad(const Geom& g, const __half* x, const __half* dy, float* dw, void* ws, hipStream_t st);
 
 }  // namespace sdconv

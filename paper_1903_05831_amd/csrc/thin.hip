@@ -145,11 +145,24 @@ __global__ __launch_bounds__(256) void thin_fwd_kernel(ThinParams P)
 #pragma unroll
                 for (int q = 0; q < 4; ++q) {
                     int k = kb * 32 + 8 * q + 4 * lhi;
+                    float v[4] = {acc[row][kb][4 * q + 0], acc[row][kb][4 * q + 1], acc[row][kb][4 * q + 2],
+                                  acc[row][kb][4 * q + 3]};
+                    if (P.ep.any()) {
+                        const int ho = ho0 + pix / kTW, wo = wo0 + pix % kTW;
+                        if (ho < P.Ho && wo < P.Wo) {
+                            const long o = (((long)n * P.Ho + ho) * P.Wo + wo) * P.K;
+#pragma unroll
+                            for (int e = 0; e < 4; ++e) {
+                                const int kk = kt * kKT + k + e;
+                                if (kk < P.K) v[e] = epilogue_apply(P.ep, v[e], kk, o + kk);
+                            }
+                        }
+                    }
                     half4 h;
-                    h[0] = (_Float16)acc[row][kb][4 * q + 0];
-                    h[1] = (_Float16)acc[row][kb][4 * q + 1];
-                    h[2] = (_Float16)acc[row][kb][4 * q + 2];
-                    h[3] = (_Float16)acc[row][kb][4 * q + 3];
+                    h[0] = (_Float16)v[0];
+                    h[1] = (_Float16)v[1];
+                    h[2] = (_Float16)v[2];
+                    h[3] = (_Float16)v[3];
                     int chunk = (k >> 3) ^ (pix & 7);
                     *reinterpret_cast<half4*>(stage + pix * 128 + chunk * 16 + (k & 7) * 2) = h;
                 }
@@ -364,18 +377,20 @@ __global__ __launch_bounds__(256) void thin_dgrad_kernel(ThinDgradParams P)
         }
     }
     if (live) {
-        __half* out = P.DX + (((long)n * P.H + (ca + P.sh * i)) * P.W + (cb + P.sw * j)) * P.C;
+        const long o = (((long)n * P.H + (ca + P.sh * i)) * P.W + (cb + P.sw * j)) * P.C;
 #pragma unroll
         for (int c = 0; c < 4; ++c)
-            if (c < P.C) out[c] = __float2half_rn(acc[c]);
+            if (c < P.C) P.DX[o + c] = __float2half_rn(epilogue_apply(P.ep, acc[c], c, o + c));
     }
 }
 
 size_t thin_dgrad_lds_bytes(const Geom& g) { return (size_t)g.C * g.R * g.S * g.K * 2; }
 
-hipError_t launch_thin_dgrad(const Geom& g, const __half* dy, const __half* wT, __half* dx, hipStream_t st)
+hipError_t launch_thin_dgrad(const Geom& g, const __half* dy, const __half* wT, __half* dx, hipStream_t st,
+                             const Epilogue& ep)
 {
     ThinDgradParams P;
+    P.ep = ep;
     P.G = dy; P.WT = wT; P.DX = dx;
     P.N = g.N; P.H = g.H; P.W = g.W; P.C = g.C; P.K = g.K; P.R = g.R; P.S = g.S;
     P.sh = g.sh; P.sw = g.sw; P.ph = g.ph; P.pw = g.pw; P.dh = g.dh; P.dw = g.dw; P.Ho = g.Ho; P.Wo = g.Wo;
@@ -436,7 +451,8 @@ bool thin_supported(const Geom& g)
     return fwd_lds <= 150 * 1024;
 }
 
-hipError_t launch_thin_fwd(const Geom& g, const __half* x, const __half* w, __half* y, void* ws, hipStream_t st)
+hipError_t launch_thin_fwd(const Geom& g, const __half* x, const __half* w, __half* y, void* ws, hipStream_t st,
+                           const Epilogue& ep)
 {
     ThinParams P = make_params(g);
     int ktiles = (g.K + kKT - 1) / kKT;
@@ -447,6 +463,7 @@ hipError_t launch_thin_fwd(const Geom& g, const __half* x, const __half* w, __ha
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     P.X = x; P.Wp = wp; P.Y = y;
+    P.ep = ep;
     size_t lds = (size_t)g.R * 4 * kKT * 16 + (((size_t)P.PH * P.PW * 8 + 15) & ~(size_t)15) + 256 * 128;
     static bool configured = false;
     if (!configured) {

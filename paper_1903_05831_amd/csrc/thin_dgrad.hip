@@ -117,10 +117,10 @@ __global__ __launch_bounds__(256) void thin_dgrad_mfma_kernel(ThinDgradMfmaParam
         }
         const int h = (i0 + ii) * P.sh + ca, w = (j0 + jseg + ncol) * P.sw + cb;
         if (cls < P.sh * P.sw && h < P.H && w < P.W) {
-            __half* out = P.DX + (((long)n * P.H + h) * P.W + w) * P.C;
+            const long o = (((long)n * P.H + h) * P.W + w) * P.C;
 #pragma unroll
             for (int c = 0; c < 4; ++c)
-                if (c < P.C) out[c] = __float2half_rn(acc[c]);
+                if (c < P.C) P.DX[o + c] = __float2half_rn(epilogue_apply(P.ep, acc[c], c, o + c));
         }
     }
 }
@@ -176,10 +176,11 @@ size_t thin_dgrad_mfma_workspace_bytes(const Geom& g)
 }
 
 hipError_t launch_thin_dgrad_mfma(const Geom& g, const __half* dy, const __half* w, __half* dx, void* ws,
-                                  hipStream_t st)
+                                  hipStream_t st, const Epilogue& ep)
 {
     ThinDgradMfmaParams P;
     if (!make_mfma_params(g, &P)) return hipErrorInvalidValue;
+    P.ep = ep;
     __half* wm = static_cast<__half*>(ws);
     P.G = dy; P.Wm = wm; P.DX = dx;
     int total = P.RP * P.SP * g.K * 16;

@@ -122,3 +122,55 @@ def check_all_passes(d, x: np.ndarray, w: np.ndarray, g: np.ndarray, tag: str, s
         else:
             idx = workloads.sample_indices(got.size, sample, seed + pass_id)
             compare(got.ravel()[idx], ofn(od, a_np, b_np, idx=idx), what + f" ({idx.size} samples)")
+
+
+def check_fused(d, x: np.ndarray, w: np.ndarray, g: np.ndarray, tag: str, seed=0, fwd_opts=None, dgrad_opts=None):
+    """Runs conv2d_fwd_fused and conv2d_dgrad_fused with seeded tails and checks the whole
+    tensors against the fused-epilogue oracle (same bar as the plain passes).
+
+    fwd_opts: subset of {"scale", "bias", "residual", "relu"}; dgrad_opts: subset of
+    {"scale", "relu_mask"}; None = everything."""
+    from oracle import epilogue as oep
+    fwd_opts = {"scale", "bias", "residual", "relu"} if fwd_opts is None else set(fwd_opts)
+    dgrad_opts = {"scale", "relu_mask"} if dgrad_opts is None else set(dgrad_opts)
+    od = oracle_desc(d)
+    ho, wo = sd.conv2d_out_shape(d)
+    rng = np.random.default_rng(seed + 12345)
+    stream = torch.cuda.current_stream().cuda_stream
+    xd, wd, gd = to_dev(x), to_dev(w), to_dev(g)
+
+    # forward: factors around 1 with both signs, a shortcut of the size of the output
+    scale = (rng.standard_normal(d.K) * 0.5 + 1.0).astype(np.float32) if "scale" in fwd_opts else None
+    bias = rng.standard_normal(d.K).astype(np.float32) if "bias" in fwd_opts else None
+    res = rng.standard_normal((d.N, ho, wo, d.K)).astype(np.float16) if "residual" in fwd_opts else None
+    relu = "relu" in fwd_opts
+    what = f"{tag} fwd_fused{sorted(fwd_opts)} [{sd.kernel_name(d, sd.FWD)}]"
+    say(f"  run {what}")
+    out = GuardedOut((d.N, ho, wo, d.K), torch.float16)
+    sd.conv2d_fwd_fused(d, xd, wd, out.view, workspace_for(d, sd.FWD), stream,
+                        scale=None if scale is None else to_dev(scale), bias=None if bias is None else to_dev(bias),
+                        residual=None if res is None else to_dev(res), relu=relu)
+    torch.cuda.synchronize()
+    out.check_guards()
+    assert out.all_written(), f"{what}: some output elements were never written"
+    compare(out.numpy(), oep.conv2d_fwd_fused(od, x, w, scale, bias, res, relu), what)
+
+    # data gradient: the mask is an activation tensor, about half of it positive, some exact zeros
+    dscale = (rng.standard_normal(d.C) * 0.5 + 1.0).astype(np.float32) if "scale" in dgrad_opts else None
+    mask = None
+    if "relu_mask" in dgrad_opts:
+        mask = np.maximum(rng.standard_normal((d.N, d.H, d.W, d.C)), 0.0).astype(np.float16)
+    what = f"{tag} dgrad_fused{sorted(dgrad_opts)} [{sd.kernel_name(d, sd.DGRAD)}]"
+    say(f"  run {what}")
+    out = GuardedOut((d.N, d.H, d.W, d.C), torch.float16)
+    sd.conv2d_dgrad_fused(d, gd, wd, out.view, workspace_for(d, sd.DGRAD), stream,
+                          scale=None if dscale is None else to_dev(dscale),
+                          relu_mask=None if mask is None else to_dev(mask))
+    torch.cuda.synchronize()
+    out.check_guards()
+    assert out.all_written(), f"{what}: some output elements were never written"
+    got = out.numpy()
+    compare(got, oep.conv2d_dgrad_fused(od, g, w, dscale, mask), what)
+    if mask is not None:
+        # the masked positions are decided on binary16 inputs: exact zeros, bit for bit
+        assert not got[mask <= 0].view(np.uint16).any(), f"{what}: masked elements must be +0"
