@@ -274,6 +274,62 @@ def main() -> int:
     torch.cuda.synchronize()
     tail_ms = e0.elapsed_time(e1) / 5
     del mw, mbuf, w16
+    # ---- fused epilogues: forward and data-gradient chains of the whole network, one stream -----
+    # every layer gets the tail it has in a residual network with frozen batch normalisation:
+    # affine + ReLU (stem, a, b), affine + shortcut + ReLU (c), affine only (projection p); the
+    # data gradients get the scale and ReLU mask of the activation that feeds the layer.
+    # Three ways: the plain pass, the fused call, the plain pass followed by a separate tail pass.
+    def tail_of(l):
+        if l.name.endswith("c"):
+            return dict(residual=True, relu=True)
+        if l.name.endswith("p"):
+            return dict(residual=False, relu=False)
+        return dict(residual=False, relu=True)
+    vecs = {}
+    for (l, d, x, w, g, y, dx, dw) in jobs:
+        for n in (l.K, l.C):
+            if n not in vecs and n % 8 == 0:
+                vecs[n] = (torch.rand(n, device=dev) + 0.5, torch.randn(n, device=dev))
+    fwd_modes = {"plain": [], "fused": [], "separate": []}
+    dg_modes = {"plain": [], "fused": [], "separate": []}
+    tail_bytes_fwd = tail_bytes_dg = 0
+    for (l, d, x, w, g, y, dx, dw) in jobs:
+        t = tail_of(l)
+        sc, bi = vecs[l.K]
+        res = g if t["residual"] else None          # a tensor of y's shape stands in for the shortcut
+        npix = l.N * l.Ho * l.Wo
+        fwd_modes["plain"].append(lambda d=d, x=x, w=w, y=y: sd.conv2d_fwd(d, x, w, y, ws, stream))
+        fwd_modes["fused"].append(lambda d=d, x=x, w=w, y=y, sc=sc, bi=bi, res=res, r=t["relu"]:
+                                  sd.conv2d_fwd_fused(d, x, w, y, ws, stream, scale=sc, bias=bi, residual=res, relu=r))
+        fwd_modes["separate"].append(lambda d=d, x=x, w=w, y=y, sc=sc, bi=bi, res=res, r=t["relu"], npix=npix, K=l.K:
+                                     (sd.conv2d_fwd(d, x, w, y, ws, stream),
+                                      sd.sdconv_tail_pass(y, npix, K, stream, scale=sc, bias=bi, residual=res, relu=r)))
+        tail_bytes_fwd += 2 * y.numel() * (3 if t["residual"] else 2)
+        if l.C % 8:
+            continue                                 # the stem: no gradient with respect to the image
+        scc = vecs[l.C][0]
+        nin = l.N * l.H * l.W
+        dg_modes["plain"].append(lambda d=d, g=g, w=w, dx=dx: sd.conv2d_dgrad(d, g, w, dx, ws, stream))
+        dg_modes["fused"].append(lambda d=d, g=g, w=w, dx=dx, scc=scc, x=x:
+                                 sd.conv2d_dgrad_fused(d, g, w, dx, ws, stream, scale=scc, relu_mask=x))
+        dg_modes["separate"].append(lambda d=d, g=g, w=w, dx=dx, scc=scc, x=x, nin=nin, C=l.C:
+                                    (sd.conv2d_dgrad(d, g, w, dx, ws, stream),
+                                     sd.sdconv_tail_pass(dx, nin, C, stream, scale=scc, relu_mask=x)))
+        tail_bytes_dg += 2 * dx.numel() * 3
+
+    def time_chain(fns, reps=3):
+        for f in fns:
+            f()
+        torch.cuda.synchronize()
+        e0.record()
+        for _ in range(reps):
+            for f in fns:
+                f()
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / reps
+    fused_ms = {"fwd": {k: time_chain(v) for k, v in fwd_modes.items()},
+                "dgrad": {k: time_chain(v) for k, v in dg_modes.items()}}
     # what the matrix pipes sustain with nothing else in the way (see sdconv_mfma_ceiling)
     props = torch.cuda.get_device_properties(dev)
     cus = props.multi_processor_count
@@ -316,6 +372,12 @@ def main() -> int:
                            "us": tail_ms * 1e3, "bytes": 30 * dw_total,
                            "GBps": 30.0 * dw_total / tail_ms / 1e6,
                            "frac_hbm": 30.0 * dw_total / tail_ms / 1e6 / PEAK_HBM_GBS},
+        "fused_epilogue": {
+            "what": "forward / data-gradient chains of all layers on one stream: plain pass, fused tail "
+                    "(frozen-BN affine, shortcut on the c layers, ReLU; scale + ReLU mask in the data gradient), "
+                    "plain pass + separate in-place tail pass",
+            "fwd_ms": fused_ms["fwd"], "dgrad_ms": fused_ms["dgrad"],
+            "separate_pass_algorithmic_bytes": {"fwd": tail_bytes_fwd, "dgrad": tail_bytes_dg}},
         "device": {"name": props.name, "compute_units": cus, "mfma_only_tflops": ceiling_tflops, "mfma_only_frac_of_peak": ceiling_tflops / PEAK_F16_TFLOPS},
         "ms_per_step_with_events": instrumented_ms,
         "one_stream_events": {"tflops": flops_per_step / instrumented_ms / 1e9,

@@ -197,6 +197,18 @@ const char *sdconv_kernel_name(const conv2d_desc *desc, int pass);
  * counts. */
 int sdconv_mfma_ceiling(float *scratch, int blocks, int iters, void *hip_stream);
 
+/* Measurement aid: the elementwise tail of conv2d_fwd_fused / conv2d_dgrad_fused as a separate
+ * in-place pass over t, a binary16 [pixels][channels] tensor (what runs after a convolution
+ * when the tail is not fused; it reads and writes the whole activation once more, and rounds
+ * to binary16 twice where the fused calls round once):
+ *   v = t[p][c]; v *= scale[c]; v += bias[c]; v += residual[p][c]; relu: v = max(v, 0);
+ *   relu_mask: v = relu_mask[p][c] > 0 ? v : 0;  t[p][c] = binary16(v)
+ * with binary32 arithmetic; NULL pointers / relu == 0 leave a step out.  All pointers are
+ * device pointers, 16-byte aligned; channels must be a multiple of 8.  Asynchronous on
+ * hip_stream.  SDCONV_EINVAL for a null t, bad sizes or misalignment. */
+int sdconv_tail_pass(void *t, size_t pixels, int32_t channels, const float *scale, const float *bias,
+                     const void *residual, const void *relu_mask, int32_t relu, void *hip_stream);
+
 #ifdef __cplusplus
 }
 #endif

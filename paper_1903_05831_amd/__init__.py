@@ -22,7 +22,7 @@ EXPORTS = (
     "conv2d_out_shape", "conv2d_workspace_bytes", "conv2d_fwd", "conv2d_dgrad", "conv2d_wgrad",
     "grad_unscale_check", "sdconv_status_string", "sdconv_last_hip_error", "sdconv_kernel_name",
     "sdconv_mfma_ceiling", "grad_unscale_check_dynamic", "sgd_momentum_update",
-    "conv2d_fwd_fused", "conv2d_dgrad_fused",
+    "conv2d_fwd_fused", "conv2d_dgrad_fused", "sdconv_tail_pass",
 )
 
 
@@ -85,6 +85,8 @@ def lib() -> ctypes.CDLL:
         L.conv2d_fwd_fused.restype = ctypes.c_int
         L.conv2d_dgrad_fused.argtypes = [dp, vp, vp, ctypes.POINTER(conv2d_dgrad_epilogue), vp, vp, sz, vp]
         L.conv2d_dgrad_fused.restype = ctypes.c_int
+        L.sdconv_tail_pass.argtypes = [vp, sz, ctypes.c_int32, vp, vp, vp, vp, ctypes.c_int32, vp]
+        L.sdconv_tail_pass.restype = ctypes.c_int
         L.sdconv_mfma_ceiling.argtypes = [vp, ctypes.c_int, ctypes.c_int, vp]
         L.sdconv_mfma_ceiling.restype = ctypes.c_int
         _lib = L
@@ -175,6 +177,15 @@ def conv2d_dgrad_fused(desc, dy, w, dx, workspace=None, stream: int = 0, *, scal
                                   stream or 0)
     if rc:
         raise SdconvError(rc, "conv2d_dgrad_fused")
+
+
+def sdconv_tail_pass(t, pixels: int, channels: int, stream: int = 0, *, scale=None, bias=None, residual=None,
+                     relu_mask=None, relu: bool = False) -> None:
+    """Measurement aid: the elementwise tail as a separate in-place pass over t [pixels][channels] fp16."""
+    rc = lib().sdconv_tail_pass(_ptr(t), pixels, channels, _ptr(scale) or None, _ptr(bias) or None,
+                                _ptr(residual) or None, _ptr(relu_mask) or None, 1 if relu else 0, stream or 0)
+    if rc:
+        raise SdconvError(rc, "sdconv_tail_pass")
 
 
 def conv2d_wgrad(desc, x, dy, dw, workspace=None, stream: int = 0) -> None:

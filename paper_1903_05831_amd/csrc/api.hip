@@ -222,6 +222,19 @@ extern "C" __attribute__((visibility("default"))) const char* sdconv_kernel_name
 
 namespace sdconv { hipError_t launch_mfma_ceiling(float* out, int blocks, int iters, hipStream_t st); }
 
+extern "C" __attribute__((visibility("default"))) int sdconv_tail_pass(void* t, size_t pixels, int32_t channels,
+                                                                       const float* scale, const float* bias,
+                                                                       const void* residual, const void* relu_mask,
+                                                                       int32_t relu, void* hip_stream)
+{
+    if (!t || channels <= 0 || channels % 8 || pixels == 0 || pixels * (size_t)channels >= ((size_t)1 << 31))
+        return SDCONV_EINVAL;
+    if (!aligned16(t) || !aligned16(scale) || !aligned16(bias) || !aligned16(residual) || !aligned16(relu_mask))
+        return SDCONV_EINVAL;
+    Epilogue E{scale, bias, static_cast<const __half*>(residual), static_cast<const __half*>(relu_mask), relu ? 1 : 0};
+    return hip_status(launch_tail_pass(static_cast<__half*>(t), (long)pixels, channels, E, (hipStream_t)hip_stream));
+}
+
 extern "C" __attribute__((visibility("default"))) int sdconv_mfma_ceiling(float* scratch, int blocks, int iters,
                                                                           void* hip_stream)
 {

@@ -75,6 +75,7 @@ hipError_t launch_direct_fwd(const Geom& g, const __half* x, const __half* w, __
 hipError_t launch_direct_dgrad(const Geom& g, const __half* dy, const __half* w, __half* dx, hipStream_t st,
                                const Epilogue& ep = no_epilogue());
 hipError_t launch_direct_wgrad(const Geom& g, const __half* x, const __half* dy, float* dw, hipStream_t st);
+hipError_t launch_tail_pass(__half* t, long pixels, int C, const Epilogue& ep, hipStream_t st);
 hipError_t launch_unscale_check(float* grad, size_t n, float inv_scale, const float* scale_on_device,
                                 int32_t* flag, hipStream_t st);
 hipError_t launch_sgd_momentum(float* w, float* mom, const float* g, void* w16, size_t n, float lr, float mu,

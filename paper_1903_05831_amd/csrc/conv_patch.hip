@@ -40,7 +40,7 @@ typedef float float4p __attribute__((ext_vector_type(4)));
 // TPS: taps per pipeline step (must divide R*S).  A step of one tap is only 64 deep; on small
 // tiles the barrier and the wait then cost as much as the MFMAs between them, so a step can
 // cover a whole filter row (TPS = 3): the ring stage holds TPS filter slabs.
-template <int MODE, int TH, int TW, int BN, int WGM, int WGN, int SB, int MF = 32, int NIW = 0, int TPS = 1>
+template <int MODE, int TH, int TW, int BN, int WGM, int WGN, int SB, int MF = 32, int NIW = 0, int TPS = 1, bool TAIL = false>
 __global__ __launch_bounds__(64 * WGM * WGN) void conv_patch_kernel(IgemmParams P)
 {
     constexpr int EH = 2, EW = 2;                   // extra patch rows / columns
@@ -248,7 +248,7 @@ __global__ __launch_bounds__(64 * WGM * WGN) void conv_patch_kernel(IgemmParams 
     static_assert(NW * epilogue_strip_bytes<WN, MF>() <= 2 * PATCHB + SB * TPS * BN * 128,
                   "epilogue strips fit in the patch buffers and the filter ring");
     __builtin_amdgcn_s_barrier();                   // everybody is done reading the last patch and filter stage
-    store_rows_via_lds<FM, FN, MF>(acc, smem + wave * epilogue_strip_bytes<WN, MF>(), lane, n0 + wn * WN, P,
+    store_rows_via_lds<FM, FN, MF, TAIL>(acc, smem + wave * epilogue_strip_bytes<WN, MF>(), lane, n0 + wn * WN, P,
                                [&](int r) -> long {
         const int ml = wm * WM + r;
         const int h = h0 + ml / TW, w = w0 + ml % TW;
@@ -257,8 +257,8 @@ __global__ __launch_bounds__(64 * WGM * WGN) void conv_patch_kernel(IgemmParams 
     });
 }
 
-template <int MODE, int TH, int TW, int BN, int WGM, int WGN, int SB, int MF = 32, int NIW = 0, int TPS = 1>
-static hipError_t launch_patch_variant(const IgemmParams& P, hipStream_t st)
+template <int MODE, int TH, int TW, int BN, int WGM, int WGN, int SB, int MF = 32, int NIW = 0, int TPS = 1, bool TAIL>
+static hipError_t launch_patch_variant_impl(const IgemmParams& P, hipStream_t st)
 {
     if ((P.R * P.S) % TPS != 0 || (P.R * P.S) / TPS < SB - 1) return hipErrorInvalidValue;
     constexpr int NI = NIW ? NIW : WGM * WGN / 2;
@@ -268,15 +268,22 @@ static hipError_t launch_patch_variant(const IgemmParams& P, hipStream_t st)
     static bool configured = false;
     if (!configured) {
         hipError_t e = hipFuncSetAttribute(
-            reinterpret_cast<const void*>(&conv_patch_kernel<MODE, TH, TW, BN, WGM, WGN, SB, MF, NIW, TPS>),
+            reinterpret_cast<const void*>(&conv_patch_kernel<MODE, TH, TW, BN, WGM, WGN, SB, MF, NIW, TPS, TAIL>),
             hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         if (e != hipSuccess) return e;
         configured = true;
     }
     const int grid = ((P.total_tiles + 63) / 64) * 64;
-    hipLaunchKernelGGL((conv_patch_kernel<MODE, TH, TW, BN, WGM, WGN, SB, MF, NIW, TPS>), dim3(grid), dim3(64 * WGM * WGN),
+    hipLaunchKernelGGL((conv_patch_kernel<MODE, TH, TW, BN, WGM, WGN, SB, MF, NIW, TPS, TAIL>), dim3(grid), dim3(64 * WGM * WGN),
                        lds, st, P);
     return hipGetLastError();
+}
+
+template <int MODE, int TH, int TW, int BN, int WGM, int WGN, int SB, int MF = 32, int NIW = 0, int TPS = 1>
+static hipError_t launch_patch_variant(const IgemmParams& P, hipStream_t st)
+{
+    // the tail has kernels of its own: see store_rows_via_lds
+    return P.ep.any() ? launch_patch_variant_impl<MODE, TH, TW, BN, WGM, WGN, SB, MF, NIW, TPS, true>(P, st) : launch_patch_variant_impl<MODE, TH, TW, BN, WGM, WGN, SB, MF, NIW, TPS, false>(P, st);
 }
 
 const PatchVariant kPatchVariants[kNumPatchVariants] = {

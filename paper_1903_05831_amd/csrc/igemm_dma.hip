@@ -40,7 +40,7 @@ template <int BM, int BN, int WGM, int WGN, int S, int BK> constexpr size_t dma_
     return loop > strips ? loop : strips;
 }
 
-template <int MODE, int BM, int BN, int WGM, int WGN, int S, int BK>
+template <int MODE, int BM, int BN, int WGM, int WGN, int S, int BK, bool TAIL = false>
 __global__ __launch_bounds__(64 * WGM * WGN) void igemm_dma_kernel(IgemmParams P)
 {
     constexpr int NW = WGM * WGN, NT = 64 * NW;
@@ -235,26 +235,33 @@ __global__ __launch_bounds__(64 * WGM * WGN) void igemm_dma_kernel(IgemmParams P
     // (the strips may run over the tap tables behind the ring: those are dead by now)
     static_assert(NW * epilogue_strip_bytes<WN>() <= dma_lds_bytes<BM, BN, WGM, WGN, S, BK>(), "epilogue strips fit in LDS");
     __builtin_amdgcn_s_barrier();                   // everybody is done reading the last stage
-    store_tile_via_lds<FM, FN>(acc, smem + wave * epilogue_strip_bytes<WN>(), lane, m0 + wm * WM, n0 + wn * WN,
+    store_tile_via_lds<FM, FN, 32, TAIL>(acc, smem + wave * epilogue_strip_bytes<WN>(), lane, m0 + wm * WM, n0 + wn * WN,
                                Mcls, P, Hi, Wj, eh, ew, ca, cb);
 }
 
-template <int MODE, int BM, int BN, int WGM, int WGN, int S, int BK>
-static hipError_t launch_dma_variant(const IgemmParams& P, hipStream_t st)
+template <int MODE, int BM, int BN, int WGM, int WGN, int S, int BK, bool TAIL>
+static hipError_t launch_dma_variant_impl(const IgemmParams& P, hipStream_t st)
 {
     constexpr size_t lds = dma_lds_bytes<BM, BN, WGM, WGN, S, BK>();
     static_assert(lds <= 160 * 1024, "LDS budget");
     static bool configured = false;
     if (!configured) {
         hipError_t e = hipFuncSetAttribute(
-            reinterpret_cast<const void*>(&igemm_dma_kernel<MODE, BM, BN, WGM, WGN, S, BK>),
+            reinterpret_cast<const void*>(&igemm_dma_kernel<MODE, BM, BN, WGM, WGN, S, BK, TAIL>),
             hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         if (e != hipSuccess) return e;
         configured = true;
     }
     const int grid = ((P.total_tiles + 63) / 64) * 64;   // whole runs of 8 tiles on each of 8 XCDs
-    hipLaunchKernelGGL((igemm_dma_kernel<MODE, BM, BN, WGM, WGN, S, BK>), dim3(grid), dim3(64 * WGM * WGN), lds, st, P);
+    hipLaunchKernelGGL((igemm_dma_kernel<MODE, BM, BN, WGM, WGN, S, BK, TAIL>), dim3(grid), dim3(64 * WGM * WGN), lds, st, P);
     return hipGetLastError();
+}
+
+template <int MODE, int BM, int BN, int WGM, int WGN, int S, int BK>
+static hipError_t launch_dma_variant(const IgemmParams& P, hipStream_t st)
+{
+    // the tail has kernels of its own: see store_rows_via_lds
+    return P.ep.any() ? launch_dma_variant_impl<MODE, BM, BN, WGM, WGN, S, BK, true>(P, st) : launch_dma_variant_impl<MODE, BM, BN, WGM, WGN, S, BK, false>(P, st);
 }
 
 const IgemmVariant kIgemmDmaVariants[kNumIgemmDmaVariants] = {

@@ -42,7 +42,9 @@ __device__ __forceinline__ void strip_handover()
 // MF = 32: accumulators of v_mfma_f32_32x32x16_f16 blocks (16 floats per lane: row lane%32,
 // columns 8q + 4*(lane/32) + j); MF = 16: of v_mfma_f32_16x16x32_f16 blocks (4 floats per lane:
 // row lane%16, columns 4*(lane/16) + j).  Both as produced by mfma(B fragment, A fragment).
-template <int FM, int FN, int MF = 32, typename Acc, typename PixOf>
+// TAIL: compiled with the elementwise tail (P.ep); the kernels are instantiated both ways so that
+// the plain passes keep the registers (and the occupancy) they have without it.
+template <int FM, int FN, int MF = 32, bool TAIL = false, typename Acc, typename PixOf>
 __device__ __forceinline__ void store_rows_via_lds(Acc (&acc)[FN][FM], unsigned char* strip, int lane,
                                                    int col_base, const IgemmParams& P, PixOf pix_of)
 {
@@ -57,7 +59,7 @@ __device__ __forceinline__ void store_rows_via_lds(Acc (&acc)[FN][FM], unsigned 
     const int srow = lane / CW, schunk = lane % CW;
     const int col = col_base + schunk * 8;          // first of this lane's 8 destination channels
 
-    if (!P.ep.any()) {
+    if constexpr (!TAIL) {
         constexpr int PITCH = WN * 2 + 16;
 #pragma unroll
         for (int b = 0; b < FM; ++b) {
@@ -87,11 +89,10 @@ __device__ __forceinline__ void store_rows_via_lds(Acc (&acc)[FN][FM], unsigned 
             }
             strip_handover();
         }
-        return;
-    }
-
+    } else {
     // ---- with the elementwise tail: fp32 strip ------------------------------------------------
     constexpr int PITCH = WN * 4 + 16;
+    constexpr int NJ = (MF + RPI - 1) / RPI;        // read-back instructions per block row
     const Epilogue& E = P.ep;
     const bool live = col < P.Cd;                   // Cd is a multiple of 8 on this route: all 8 or none
     f4 sc0 = {1.f, 1.f, 1.f, 1.f}, sc1 = sc0, bi0 = {0.f, 0.f, 0.f, 0.f}, bi1 = bi0;
@@ -103,6 +104,22 @@ __device__ __forceinline__ void store_rows_via_lds(Acc (&acc)[FN][FM], unsigned 
         bi0 = *reinterpret_cast<const f4*>(E.bias + col);
         bi1 = *reinterpret_cast<const f4*>(E.bias + col + 4);
     }
+    // Destination offsets of everything this lane will store, and the shortcut (or, without
+    // one, the mask) values that go with them: all loads are sent before the first strip is
+    // written, so their latency passes behind the LDS work instead of once per block row.
+    const _Float16* aux = reinterpret_cast<const _Float16*>(E.residual ? E.residual : E.mask);
+    int off[FM][NJ];
+    h8 pre[FM][NJ];
+#pragma unroll
+    for (int b = 0; b < FM; ++b)
+#pragma unroll
+        for (int j = 0; j < NJ; ++j) {
+            const int r = j * RPI + srow;
+            const bool mine = RPI <= MF || r < MF;  // (there may be more lanes than strip chunks)
+            const long pix = (mine && live) ? pix_of(b * MF + r) : -1;
+            off[b][j] = pix >= 0 ? (int)(pix * P.Cd + col) : -1;
+            if (aux && off[b][j] >= 0) pre[b][j] = *reinterpret_cast<const h8*>(aux + off[b][j]);
+        }
 #pragma unroll
     for (int b = 0; b < FM; ++b) {
 #pragma unroll
@@ -120,17 +137,11 @@ __device__ __forceinline__ void store_rows_via_lds(Acc (&acc)[FN][FM], unsigned 
         }
         strip_handover();
 #pragma unroll
-        for (int j = 0; j < (MF + RPI - 1) / RPI; ++j) {
+        for (int j = 0; j < NJ; ++j) {
             const int r = j * RPI + srow;
-            const bool mine = RPI <= MF || r < MF;      // (there may be more lanes than strip chunks)
-            f4 v0 = {0.f, 0.f, 0.f, 0.f}, v1 = v0;
-            if (mine) {
-                v0 = *reinterpret_cast<const f4*>(strip + r * PITCH + schunk * 32);
-                v1 = *reinterpret_cast<const f4*>(strip + r * PITCH + schunk * 32 + 16);
-            }
-            const long pix = mine ? pix_of(b * MF + r) : -1;
-            if (pix < 0 || !live) continue;
-            const long i = pix * P.Cd + col;
+            if (off[b][j] < 0) continue;            // (such a lane reads nothing it would need)
+            f4 v0 = *reinterpret_cast<const f4*>(strip + r * PITCH + schunk * 32);
+            f4 v1 = *reinterpret_cast<const f4*>(strip + r * PITCH + schunk * 32 + 16);
             float v[8];
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
@@ -138,37 +149,38 @@ __device__ __forceinline__ void store_rows_via_lds(Acc (&acc)[FN][FM], unsigned 
                 v[4 + e] = v1[e] * sc1[e] + bi1[e];
             }
             if (E.residual) {
-                h8 rr = *reinterpret_cast<const h8*>(reinterpret_cast<const _Float16*>(E.residual) + i);
 #pragma unroll
-                for (int e = 0; e < 8; ++e) v[e] += (float)rr[e];
+                for (int e = 0; e < 8; ++e) v[e] += (float)pre[b][j][e];
             }
             if (E.relu) {
 #pragma unroll
                 for (int e = 0; e < 8; ++e) v[e] = v[e] > 0.f ? v[e] : 0.f;
             }
             if (E.mask) {
-                h8 mm = *reinterpret_cast<const h8*>(reinterpret_cast<const _Float16*>(E.mask) + i);
+                h8 mm = pre[b][j];
+                if (E.residual) mm = *reinterpret_cast<const h8*>(reinterpret_cast<const _Float16*>(E.mask) + off[b][j]);
 #pragma unroll
                 for (int e = 0; e < 8; ++e) v[e] = (float)mm[e] > 0.f ? v[e] : 0.f;
             }
             h8 o;
 #pragma unroll
             for (int e = 0; e < 8; ++e) o[e] = (_Float16)v[e];
-            *reinterpret_cast<h8*>(P.D + i) = o;
+            *reinterpret_cast<h8*>(P.D + off[b][j]) = o;
         }
         strip_handover();
+    }
     }
 }
 
 // Rows are GEMM rows m_base.. of an implicit-GEMM tile (pixels of one stride-parity class in
 // (n, i, j) order; eh/ew/ca/cb place class pixel (i, j) at (i*eh + ca, j*ew + cb)).
-template <int FM, int FN, int MF = 32, typename Acc>
+template <int FM, int FN, int MF = 32, bool TAIL = false, typename Acc>
 __device__ __forceinline__ void store_tile_via_lds(Acc (&acc)[FN][FM], unsigned char* strip, int lane,
                                                    int m_base, int col_base, int Mcls, const IgemmParams& P,
                                                    int Hi, int Wj, int eh, int ew, int ca, int cb)
 {
     const bool linear = (eh == 1 && ew == 1);       // destination pixel index == GEMM row index
-    store_rows_via_lds<FM, FN, MF>(acc, strip, lane, col_base, P, [&](int r) -> long {
+    store_rows_via_lds<FM, FN, MF, TAIL>(acc, strip, lane, col_base, P, [&](int r) -> long {
         const int m = m_base + r;
         if (m >= Mcls) return -1;
         if (linear) return m;

@@ -37,7 +37,7 @@ typedef float float4v_ __attribute__((ext_vector_type(4)));
 // MF: 32 = v_mfma_f32_32x32x16_f16 blocks; 16 = v_mfma_f32_16x16x32_f16 blocks, for tile heights
 // that are a multiple of 16 but not of 32 per wave row (224 = 2 x 112 rows: 25088 = 112 x 224
 // pixels of the RoI head then give 224 or 896 tiles instead of 196 or 784 for 256 CUs).
-template <int MODE, int BM, int BN, int WGM, int WGN, int S, int BK, int NP, int MF = 32>
+template <int MODE, int BM, int BN, int WGM, int WGN, int S, int BK, int NP, int MF = 32, bool TAIL = false>
 __global__ __launch_bounds__(64 * (WGM * WGN + NP)) void igemm_ws_kernel(IgemmParams P)
 {
     constexpr int NWC = WGM * WGN;                  // multiplying waves
@@ -318,27 +318,34 @@ __global__ __launch_bounds__(64 * (WGM * WGN + NP)) void igemm_ws_kernel(IgemmPa
     // ---- epilogue: through a per-wave LDS strip into 16-byte NHWC stores --------------------
     static_assert(NWC * epilogue_strip_bytes<WN, MF>() <= S * STAGE, "epilogue strips fit in the ring");
     __builtin_amdgcn_s_barrier();                   // everybody is done reading the last stage
-    store_tile_via_lds<FM, FN, MF>(acc, smem + wave * epilogue_strip_bytes<WN, MF>(), lane, m0 + wm * WM, n0 + wn * WN,
+    store_tile_via_lds<FM, FN, MF, TAIL>(acc, smem + wave * epilogue_strip_bytes<WN, MF>(), lane, m0 + wm * WM, n0 + wn * WN,
                                Mcls, P, Hi, Wj, eh, ew, ca, cb);
 }
 
-template <int MODE, int BM, int BN, int WGM, int WGN, int S, int BK, int NP, int MF = 32>
-static hipError_t launch_ws_variant(const IgemmParams& P, hipStream_t st)
+template <int MODE, int BM, int BN, int WGM, int WGN, int S, int BK, int NP, int MF = 32, bool TAIL>
+static hipError_t launch_ws_variant_impl(const IgemmParams& P, hipStream_t st)
 {
     constexpr size_t lds = (size_t)S * (BM + BN) * BK * 2 + (4 * kMaxTaps + 4) * sizeof(int) + (size_t)BM * 12;
     static_assert(lds <= 160 * 1024, "LDS budget");
     static bool configured = false;
     if (!configured) {
         hipError_t e = hipFuncSetAttribute(
-            reinterpret_cast<const void*>(&igemm_ws_kernel<MODE, BM, BN, WGM, WGN, S, BK, NP, MF>),
+            reinterpret_cast<const void*>(&igemm_ws_kernel<MODE, BM, BN, WGM, WGN, S, BK, NP, MF, TAIL>),
             hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         if (e != hipSuccess) return e;
         configured = true;
     }
     const int grid = ((P.total_tiles + 63) / 64) * 64;   // whole runs of 8 tiles on each of 8 XCDs
-    hipLaunchKernelGGL((igemm_ws_kernel<MODE, BM, BN, WGM, WGN, S, BK, NP, MF>), dim3(grid),
+    hipLaunchKernelGGL((igemm_ws_kernel<MODE, BM, BN, WGM, WGN, S, BK, NP, MF, TAIL>), dim3(grid),
                        dim3(64 * (WGM * WGN + NP)), lds, st, P);
     return hipGetLastError();
+}
+
+template <int MODE, int BM, int BN, int WGM, int WGN, int S, int BK, int NP, int MF = 32>
+static hipError_t launch_ws_variant(const IgemmParams& P, hipStream_t st)
+{
+    // the tail has kernels of its own: see store_rows_via_lds
+    return P.ep.any() ? launch_ws_variant_impl<MODE, BM, BN, WGM, WGN, S, BK, NP, MF, true>(P, st) : launch_ws_variant_impl<MODE, BM, BN, WGM, WGN, S, BK, NP, MF, false>(P, st);
 }
 
 const IgemmVariant kIgemmWsVariants[kNumIgemmWsVariants] = {

@@ -104,3 +104,27 @@ def test_fused_argument_checks():
         sd.conv2d_fwd_fused(d, xd, wd, y, None, 0, scale=sc[1:9])          # 4-byte aligned only
     with pytest.raises(sd.SdconvError):
         sd.conv2d_dgrad_fused(d, y, wd, xd.clone(), None, 0, relu_mask=xd.view(-1)[1:])  # 2-byte aligned
+
+
+def test_tail_pass_matches_the_elementwise_definition():
+    """The separate pass used as the unfused baseline in the benchmark computes the same tail
+    (on an already rounded binary16 tensor)."""
+    rng = np.random.default_rng(7)
+    pixels, C = 1237, 72
+    t = rng.standard_normal((pixels, C)).astype(np.float16)
+    scale = (rng.standard_normal(C) * 0.5 + 1).astype(np.float32)
+    bias = rng.standard_normal(C).astype(np.float32)
+    res = rng.standard_normal((pixels, C)).astype(np.float16)
+    mask = np.maximum(rng.standard_normal((pixels, C)), 0).astype(np.float16)
+    td = to_dev(t.copy())
+    sd.sdconv_tail_pass(td, pixels, C, 0, scale=to_dev(scale), bias=to_dev(bias), residual=to_dev(res),
+                        relu_mask=to_dev(mask), relu=True)
+    torch.cuda.synchronize()
+    v = t.astype(np.float64) * scale + bias + res.astype(np.float64)
+    v = np.where(v > 0, v, 0.0)
+    v = np.where(mask > 0, v, 0.0)
+    got = td.cpu().numpy().astype(np.float64)
+    assert np.all(np.abs(got - v) <= 2e-3 * (1 + np.abs(v)))
+    assert not got[mask <= 0].any()
+    with pytest.raises(sd.SdconvError):
+        sd.sdconv_tail_pass(td, pixels, 12, 0)          # channels not a multiple of 8
