@@ -330,6 +330,35 @@ def main() -> int:
         return e0.elapsed_time(e1) / reps
     fused_ms = {"fwd": {k: time_chain(v) for k, v in fwd_modes.items()},
                 "dgrad": {k: time_chain(v) for k, v in dg_modes.items()}}
+    # ---- second shape set: what a ResNet-50-FPN Faster R-CNN adds (Table 1 of the paper quotes its
+    # speed on that model): res5 on the image, FPN, RPN heads on P2-P6, box-head FCs, C4 RPN --------
+    del fwd_modes, dg_modes
+    torch.cuda.empty_cache()
+    second = {}
+    fns2, flops2 = {}, {}
+    for l in workloads.CONFIGS[6]:
+        d2 = sd.desc_of(l)
+        x2 = torch.randn(l.x_shape, device=dev, dtype=torch.float32).half()
+        w2 = (torch.randn(l.w_shape, device=dev, dtype=torch.float32) * (2.0 / (l.R * l.S * l.C)) ** 0.5).half()
+        g2 = torch.randn(l.y_shape, device=dev, dtype=torch.float32).half()
+        y2 = torch.empty(l.y_shape, dtype=torch.float16, device=dev)
+        dx2 = torch.empty(l.x_shape, dtype=torch.float16, device=dev)
+        dw2 = torch.empty(l.w_shape, dtype=torch.float32, device=dev)
+        need = max(sd.conv2d_workspace_bytes(d2, pid) for pid in (sd.FWD, sd.DGRAD, sd.WGRAD))
+        wsl = torch.empty(max(need, 256), dtype=torch.uint8, device=dev)
+        grp = l.name.split(".")[0]
+        fns2.setdefault(grp, []).extend([
+            lambda d2=d2, x2=x2, w2=w2, y2=y2, wsl=wsl: sd.conv2d_fwd(d2, x2, w2, y2, wsl, stream),
+            lambda d2=d2, g2=g2, w2=w2, dx2=dx2, wsl=wsl: sd.conv2d_dgrad(d2, g2, w2, dx2, wsl, stream),
+            lambda d2=d2, x2=x2, g2=g2, dw2=dw2, wsl=wsl: sd.conv2d_wgrad(d2, x2, g2, dw2, wsl, stream)])
+        flops2[grp] = flops2.get(grp, 0) + 3 * l.flops
+    for grp, fns in fns2.items():
+        ms = time_chain(fns)
+        second[grp] = {"ms": ms, "gflop": flops2[grp] / 1e9, "tflops": flops2[grp] / ms / 1e9}
+    second_ms = sum(v["ms"] for v in second.values())
+    second_flops = sum(flops2.values())
+    del fns2
+    torch.cuda.empty_cache()
     # what the matrix pipes sustain with nothing else in the way (see sdconv_mfma_ceiling)
     props = torch.cuda.get_device_properties(dev)
     cus = props.multi_processor_count
@@ -378,6 +407,11 @@ def main() -> int:
                     "plain pass + separate in-place tail pass",
             "fwd_ms": fused_ms["fwd"], "dgrad_ms": fused_ms["dgrad"],
             "separate_pass_algorithmic_bytes": {"fwd": tail_bytes_fwd, "dgrad": tail_bytes_dg}},
+        "second_workload": {
+            "workload": "config 6: " + workloads.CONFIG_NAMES[6],
+            "what": "fwd + dgrad + wgrad of each layer, one stream, per group of layers",
+            "layers": len(workloads.CONFIGS[6]), "ms": second_ms, "gflop": second_flops / 1e9,
+            "tflops": second_flops / second_ms / 1e9, "groups": second},
         "device": {"name": props.name, "compute_units": cus, "mfma_only_tflops": ceiling_tflops, "mfma_only_frac_of_peak": ceiling_tflops / PEAK_F16_TFLOPS},
         "ms_per_step_with_events": instrumented_ms,
         "one_stream_events": {"tflops": flops_per_step / instrumented_ms / 1e9,

@@ -52,7 +52,7 @@ __device__ __forceinline__ float epilogue_apply(const Epilogue& E, float v, int 
 }
 
 // What the dispatcher decided for one (geometry, pass).
-enum Route { ROUTE_DIRECT = 0, ROUTE_IGEMM = 1, ROUTE_THIN = 2 };
+enum Route { ROUTE_DIRECT = 0, ROUTE_IGEMM = 1, ROUTE_THIN = 2, ROUTE_PADK = 3 };
 struct Plan {
     Route route;
     int variant;             // tile variant index within the route
@@ -75,6 +75,10 @@ hipError_t launch_direct_fwd(const Geom& g, const __half* x, const __half* w, __
 hipError_t launch_direct_dgrad(const Geom& g, const __half* dy, const __half* w, __half* dx, hipStream_t st,
                                const Epilogue& ep = no_epilogue());
 hipError_t launch_direct_wgrad(const Geom& g, const __half* x, const __half* dy, float* dw, hipStream_t st);
+hipError_t launch_pad_channels(const __half* src, __half* dst, long rows, int K, int Kp, hipStream_t st);
+hipError_t launch_pad_rows(const __half* src, __half* dst, long n, long total, hipStream_t st);
+hipError_t launch_unpad_channels(const __half* yp, __half* y, long rows, int K, int Kp, const Epilogue& ep, hipStream_t st);
+hipError_t launch_copy_f32(const float* src, float* dst, long n, hipStream_t st);
 hipError_t launch_tail_pass(__half* t, long pixels, int C, const Epilogue& ep, hipStream_t st);
 hipError_t launch_unscale_check(float* grad, size_t n, float inv_scale, const float* scale_on_device,
                                 int32_t* flag, hipStream_t st);

@@ -4,6 +4,9 @@
 #include "wgrad.h"
 #include "thin.h"
 #include <stdlib.h>
+#include <map>
+#include <mutex>
+#include <string>
 
 namespace sdconv {
 
@@ -131,8 +134,38 @@ static int pick_variant(const Geom& g, bool dgrad)
 
 static bool thin_ok(const Geom& g) { return !force_direct() && g.C <= 4 && thin_supported(g); }
 
+// Filter counts that are not a multiple of 8 (with channels that are): the layer runs as one with
+// the filter count rounded up, on padded copies of the filter and of the K-channel tensor that
+// live in the workspace (padk.hip).
+static bool padk_ok(const Geom& g)
+{
+    return !force_direct() && !env_int("SDCONV_NO_PADK", 0) && g.K % 8 != 0 && g.C % 8 == 0 && g.R * g.S <= kMaxTaps &&
+           g.sh * g.sw <= kMaxClasses;
+}
+static Geom padded_k(const Geom& g) { Geom p = g; p.K = (g.K + 7) / 8 * 8; return p; }
+static size_t padk_filter_bytes(const Geom& gp) { return align256((size_t)gp.K * gp.R * gp.S * gp.C * sizeof(__half)); }
+static size_t padk_act_bytes(const Geom& gp) { return align256((size_t)gp.N * gp.Ho * gp.Wo * gp.K * sizeof(__half)); }
+static size_t padk_dw_bytes(const Geom& gp) { return align256((size_t)gp.K * gp.R * gp.S * gp.C * sizeof(float)); }
+
+// "padk+<inner kernel name>", kept for the life of the process
+static const char* padk_name(const char* inner)
+{
+    static std::mutex mu;
+    static std::map<std::string, std::string> names;
+    std::lock_guard<std::mutex> lock(mu);
+    auto it = names.find(inner);
+    if (it == names.end()) it = names.emplace(inner, std::string("padk+") + inner).first;
+    return it->second.c_str();
+}
+
 Plan plan_fwd(const Geom& g)
 {
+    if (padk_ok(g)) {
+        const Geom gp = padded_k(g);
+        const Plan in = plan_fwd(gp);
+        return Plan{ROUTE_PADK, in.variant, 1, padk_filter_bytes(gp) + padk_act_bytes(gp) + in.workspace_bytes,
+                    padk_name(in.name)};
+    }
     if (thin_ok(g)) return Plan{ROUTE_THIN, 0, 1, align256(thin_packed_filter_bytes(g)), "thin_fwd"};
     if (!igemm_ok(g)) return Plan{ROUTE_DIRECT, 0, 1, 0, "direct_fwd"};
     int v = pick_variant(g, false);
@@ -141,6 +174,12 @@ Plan plan_fwd(const Geom& g)
 
 Plan plan_dgrad(const Geom& g)
 {
+    if (padk_ok(g)) {
+        const Geom gp = padded_k(g);
+        const Plan in = plan_dgrad(gp);
+        return Plan{ROUTE_PADK, in.variant, 1, padk_filter_bytes(gp) + padk_act_bytes(gp) + in.workspace_bytes,
+                    padk_name(in.name)};
+    }
     if (!force_direct() && g.C <= 4 && thin_dgrad_mfma_supported(g) && !env_int("SDCONV_NO_THIN_MFMA_DGRAD", 0))
         return Plan{ROUTE_THIN, 1, 1, align256(thin_dgrad_mfma_workspace_bytes(g)), "thin_dgrad_mfma"};
     if (!force_direct() && g.C <= 4 && g.K % 8 == 0 && g.sh * g.sw <= kMaxClasses &&
@@ -190,6 +229,12 @@ static void wgrad_split(const Geom& g, int variant, int* splits, int* steps_per_
 
 Plan plan_wgrad(const Geom& g)
 {
+    if (padk_ok(g)) {
+        const Geom gp = padded_k(g);
+        const Plan in = plan_wgrad(gp);
+        return Plan{ROUTE_PADK, in.variant, in.splits, padk_act_bytes(gp) + padk_dw_bytes(gp) + in.workspace_bytes,
+                    padk_name(in.name)};
+    }
     if (thin_ok(g)) return Plan{ROUTE_THIN, 0, 1, align256(thin_wgrad_partial_bytes(g)), "thin_wgrad"};
     if (!igemm_ok(g)) return Plan{ROUTE_DIRECT, 0, 1, 0, "direct_wgrad"};
     int v = pick_wgrad_variant(g);
@@ -240,6 +285,21 @@ static hipError_t run_igemm(const Geom& g, const Plan& p, bool dgrad, const __ha
 hipError_t run_fwd(const Geom& g, const Plan& p, const __half* x, const __half* w, __half* y, void* ws, hipStream_t st,
                    const Epilogue& ep)
 {
+    if (p.route == ROUTE_PADK) {
+        // zero filters behind the real ones; the padded result goes to the workspace and its real
+        // channels are copied out (with the tail, if any: it sees the rounded result there)
+        const Geom gp = padded_k(g);
+        unsigned char* base = static_cast<unsigned char*>(ws);
+        __half* wp = reinterpret_cast<__half*>(base);
+        __half* yp = reinterpret_cast<__half*>(base + padk_filter_bytes(gp));
+        void* inner_ws = base + padk_filter_bytes(gp) + padk_act_bytes(gp);
+        const long wn = (long)g.K * g.R * g.S * g.C, wpn = (long)gp.K * g.R * g.S * g.C;
+        hipError_t e = launch_pad_rows(w, wp, wn, wpn, st);
+        if (e != hipSuccess) return e;
+        e = run_fwd(gp, plan_fwd(gp), x, wp, yp, inner_ws, st, no_epilogue());
+        if (e != hipSuccess) return e;
+        return launch_unpad_channels(yp, y, (long)g.N * g.Ho * g.Wo, g.K, gp.K, ep, st);
+    }
     if (p.route == ROUTE_DIRECT) return launch_direct_fwd(g, x, w, y, st, ep);
     if (p.route == ROUTE_THIN) return launch_thin_fwd(g, x, w, y, ws, st, ep);
     return run_igemm(g, p, false, x, w, y, st, ep);
@@ -248,6 +308,20 @@ hipError_t run_fwd(const Geom& g, const Plan& p, const __half* x, const __half* 
 hipError_t run_dgrad(const Geom& g, const Plan& p, const __half* dy, const __half* w, __half* dx, void* ws, hipStream_t st,
                      const Epilogue& ep)
 {
+    if (p.route == ROUTE_PADK) {
+        // zero gradient channels and zero filters behind the real ones; dx comes out in place
+        const Geom gp = padded_k(g);
+        unsigned char* base = static_cast<unsigned char*>(ws);
+        __half* wp = reinterpret_cast<__half*>(base);
+        __half* gpad = reinterpret_cast<__half*>(base + padk_filter_bytes(gp));
+        void* inner_ws = base + padk_filter_bytes(gp) + padk_act_bytes(gp);
+        const long wn = (long)g.K * g.R * g.S * g.C, wpn = (long)gp.K * g.R * g.S * g.C;
+        hipError_t e = launch_pad_rows(w, wp, wn, wpn, st);
+        if (e != hipSuccess) return e;
+        e = launch_pad_channels(dy, gpad, (long)g.N * g.Ho * g.Wo, g.K, gp.K, st);
+        if (e != hipSuccess) return e;
+        return run_dgrad(gp, plan_dgrad(gp), gpad, wp, dx, inner_ws, st, ep);
+    }
     if (p.route == ROUTE_DIRECT) return launch_direct_dgrad(g, dy, w, dx, st, ep);
     if (p.route == ROUTE_THIN && p.variant == 1) return launch_thin_dgrad_mfma(g, dy, w, dx, ws, st, ep);
     if (p.route == ROUTE_IGEMM && p.variant >= 300) return run_igemm(g, p, true, dy, w, dx, st, ep);
@@ -260,6 +334,19 @@ hipError_t run_dgrad(const Geom& g, const Plan& p, const __half* dy, const __hal
 
 hipError_t run_wgrad(const Geom& g, const Plan& p, const __half* x, const __half* dy, float* dw, void* ws, hipStream_t st)
 {
+    if (p.route == ROUTE_PADK) {
+        // zero gradient channels behind the real ones; the first K filters of the padded result are dw
+        const Geom gp = padded_k(g);
+        unsigned char* base = static_cast<unsigned char*>(ws);
+        __half* gpad = reinterpret_cast<__half*>(base);
+        float* dwp = reinterpret_cast<float*>(base + padk_act_bytes(gp));
+        void* inner_ws = base + padk_act_bytes(gp) + padk_dw_bytes(gp);
+        hipError_t e = launch_pad_channels(dy, gpad, (long)g.N * g.Ho * g.Wo, g.K, gp.K, st);
+        if (e != hipSuccess) return e;
+        e = run_wgrad(gp, plan_wgrad(gp), x, gpad, dwp, inner_ws, st);
+        if (e != hipSuccess) return e;
+        return launch_copy_f32(dwp, dw, (long)g.K * g.R * g.S * g.C, st);
+    }
     if (p.route == ROUTE_DIRECT) return launch_direct_wgrad(g, x, dy, dw, st);
     if (p.route == ROUTE_THIN) return launch_thin_wgrad(g, x, dy, dw, ws, st);
     const WgradVariant& v = wgrad_variant(p.variant);

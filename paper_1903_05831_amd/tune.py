@@ -14,6 +14,7 @@ same tensors over and over (cache-warm).
 from __future__ import annotations
 
 import argparse
+import dataclasses
 import os
 import sys
 
@@ -89,6 +90,8 @@ def main() -> int:
     ap.add_argument("--out", type=str, default=os.path.join(HERE, "csrc", "tuned_table.inc"))
     ap.add_argument("--wgrad-solo", action="store_true",
                     help="pick the weight-gradient variant by its time alone instead of beside the data gradient")
+    ap.add_argument("--keep", type=str, default="",
+                    help="an existing table: its entries for geometries not tuned in this run are kept in the output")
     ap.add_argument("--cold-mib", type=int, default=640,
                     help="rotate over copies of the inputs with this total footprint (0: one copy, cache-warm)")
     args = ap.parse_args()
@@ -102,6 +105,11 @@ def main() -> int:
     for cfg in [int(c) for c in args.configs.split(",")]:
         for l in workloads.CONFIGS[cfg]:
             key = (l.N, l.H, l.W, l.C, l.K, l.R, l.S, l.stride, l.pad, l.dil)
+            if l.C % 8 == 0 and l.K % 8:
+                # such a layer runs as one with the filter count rounded up to a multiple of 8 (the
+                # padded-filter-count route of the dispatcher): that inner layer is what gets tuned
+                l = dataclasses.replace(l, name=l.name + "+pad", K=(l.K + 7) // 8 * 8)
+                key = (l.N, l.H, l.W, l.C, l.K, l.R, l.S, l.stride, l.pad, l.dil)
             if key in seen or l.C % 8 or l.K % 8:
                 continue
             if args.layers and not any(f in l.name for f in args.layers.split(",")):
@@ -179,6 +187,17 @@ def main() -> int:
             lines.append(f"    {{{geom}, {sd.WGRAD}, {wv}, {sp}}},  // {l.name} wgrad {t*1e3:.1f} us {what}")
             del xs, wts, gs, y, dx, dw
             torch.cuda.empty_cache()
+    if args.keep:
+        def geom_and_pass(ln):      # "{N,...,dw, pass, variant, splits}, // ..." -> "{N,...,dw, pass"
+            return ln.split("},")[0].rsplit(",", 2)[0].strip()
+        fresh = {geom_and_pass(ln) for ln in lines}
+        kept = []
+        for ln in open(args.keep):
+            if not ln.lstrip().startswith("{"):
+                continue
+            if geom_and_pass(ln) not in fresh:
+                kept.append(ln.rstrip("\n"))
+        lines = kept + lines
     with open(args.out, "w") as f:
         f.write("// Written by tune.py on %s: {N,H,W,C,K,R,S,sh,sw,ph,pw,dh,dw, pass, variant, splits}\n"
                 % torch.cuda.get_device_name(0))

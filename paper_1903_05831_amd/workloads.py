@@ -130,12 +130,46 @@ def _config5() -> List[ConvLayer]:
     return out
 
 
+def _fpn_rpn() -> List[ConvLayer]:
+    """Convolutions a ResNet-50-FPN Faster R-CNN adds to (or runs differently from) the C4 model,
+    N = 2 images of 800x1344 (Table 1 of the paper quotes its training speed on this model):
+    res5 on the whole image instead of on RoIs, the FPN lateral 1x1 and output 3x3 convs at strides
+    4-32, the RPN head shared by the pyramid levels P2-P6 (3 anchors per position), the two
+    fully connected layers of the box head on 512 RoIs of 7x7x256 written as 1x1 convs on 1x1
+    images, and the RPN of the C4 model (3x3 1024->512, 15 anchors)."""
+    out = [_L("res5i.0a", 2, 50, 84, 1024, 512, 1, 1, 0, 50, 84),
+           _L("res5i.0b", 2, 50, 84, 512, 512, 3, 2, 1, 25, 42),
+           _L("res5i.0c", 2, 25, 42, 512, 2048, 1, 1, 0, 25, 42),
+           _L("res5i.0p", 2, 50, 84, 1024, 2048, 1, 2, 0, 25, 42)]
+    for i in range(1, 3):
+        q = f"res5i.{i}"
+        out += [_L(q + "a", 2, 25, 42, 2048, 512, 1, 1, 0, 25, 42),
+                _L(q + "b", 2, 25, 42, 512, 512, 3, 1, 1, 25, 42),
+                _L(q + "c", 2, 25, 42, 512, 2048, 1, 1, 0, 25, 42)]
+    levels = [(2, 200, 336, 256), (3, 100, 168, 512), (4, 50, 84, 1024), (5, 25, 42, 2048)]
+    for lv, h, w, c in levels:
+        out.append(_L(f"fpn.lat{lv}", 2, h, w, c, 256, 1, 1, 0, h, w))
+    for lv, h, w, c in levels:
+        out.append(_L(f"fpn.out{lv}", 2, h, w, 256, 256, 3, 1, 1, h, w))
+    for lv, h, w in [(2, 200, 336), (3, 100, 168), (4, 50, 84), (5, 25, 42), (6, 13, 21)]:
+        out += [_L(f"rpn.conv{lv}", 2, h, w, 256, 256, 3, 1, 1, h, w),
+                _L(f"rpn.cls{lv}", 2, h, w, 256, 3, 1, 1, 0, h, w),
+                _L(f"rpn.box{lv}", 2, h, w, 256, 12, 1, 1, 0, h, w)]
+    out += [_L("head.fc6", 512, 1, 1, 7 * 7 * 256, 1024, 1, 1, 0, 1, 1),
+            _L("head.fc7", 512, 1, 1, 1024, 1024, 1, 1, 0, 1, 1)]
+    out += [_L("c4rpn.conv", 2, 50, 84, 1024, 512, 3, 1, 1, 50, 84),
+            _L("c4rpn.cls", 2, 50, 84, 512, 15, 1, 1, 0, 50, 84),
+            _L("c4rpn.box", 2, 50, 84, 512, 60, 1, 1, 0, 50, 84)]
+    return out
+
+
 CONFIGS: Dict[int, List[ConvLayer]] = {
     1: [_L("conv3x3_64", 1, 56, 56, 64, 64, 3, 1, 1, 56, 56)],
     2: _res2_block("res2.", False),
     3: _res3_block0(),
     4: _res4(),
     5: _config5(),
+    6: _fpn_rpn(),
 }
 
 CONFIG_NAMES = {
@@ -144,6 +178,7 @@ CONFIG_NAMES = {
     3: "ResNet-50 res3 first block from 200x336x256, N=2",
     4: "ResNet-50-C4 res4 trunk (6 bottlenecks) at 50x84, N=2",
     5: "ResNet-50-C4 Faster R-CNN, all 53 convs, N=2 x 800x1344 + 512 RoIs",
+    6: "ResNet-50-FPN Faster R-CNN additions: res5 on the image, FPN, RPN heads on P2-P6, box-head FCs, C4 RPN",
 }
 
 

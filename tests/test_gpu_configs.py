@@ -1,5 +1,5 @@
 """Full-size parity on the benchmark configurations: every distinct layer shape of configs
-2-5 in the launch configuration bench.py times, checked on seeded sampled output elements
+2-5 and of the FPN / RPN shape set (6) in the launch configuration bench.py times, checked on seeded sampled output elements
 that the oracle computes one by one (each output element is an independent sum, so the
 sampled check is exact for the elements it covers)."""
 import numpy as np
@@ -19,7 +19,7 @@ SAMPLES = 3000
 
 def _distinct():
     seen, out = set(), []
-    for cfg in (2, 3, 4, 5):
+    for cfg in (2, 3, 4, 5, 6):
         for li, l in enumerate(workloads.CONFIGS[cfg]):
             key = (l.N, l.H, l.W, l.C, l.K, l.R, l.stride, l.pad)
             if key in seen:

@@ -22,6 +22,8 @@ ROUTE_SHAPES = [
     (2, 23, 29, 64, 72, 3, 3, (2, 2), (1, 1), (1, 1)),      # strided 3x3: four classes in the data gradient
     (1, 40, 50, 128, 264, 1, 1, (2, 2), (0, 0), (1, 1)),    # 1x1 stride 2: three all-zero classes
     (1, 17, 19, 136, 200, 3, 3, (1, 1), (2, 2), (2, 2)),    # dilation 2, short last channel slab
+    (2, 25, 42, 256, 12, 1, 1, (1, 1), (0, 0), (1, 1)),     # padded-filter-count route (K = 12)
+    (2, 19, 21, 16, 20, 3, 3, (2, 2), (1, 1), (1, 1)),      # ... strided 3x3, K = 20
 ]
 
 

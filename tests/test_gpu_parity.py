@@ -55,6 +55,11 @@ SMALL = [
     (1, 3, 3, 8, 8, 3, 3, (1, 1), (0, 0), (1, 1)),       # single output pixel
     (1, 1, 1, 8, 8, 1, 1, (1, 1), (0, 0), (1, 1)),       # everything is 1
     (1, 6, 6, 64, 64, 3, 3, (1, 1), (3, 3), (1, 1)),     # pad larger than needed
+    (2, 25, 42, 256, 3, 1, 1, (1, 1), (0, 0), (1, 1)),   # padded-filter-count route: RPN objectness head
+    (2, 25, 42, 256, 12, 1, 1, (1, 1), (0, 0), (1, 1)),  # ... RPN box head
+    (1, 17, 23, 512, 60, 1, 1, (1, 1), (0, 0), (1, 1)),  # ... 15-anchor box head
+    (2, 19, 21, 16, 20, 3, 3, (2, 2), (1, 1), (1, 1)),   # ... strided 3x3, K = 20
+    (1, 9, 9, 8, 1, 3, 3, (1, 1), (1, 1), (2, 2)),       # ... a single filter, dilation 2
 ]
 
 
