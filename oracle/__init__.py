@@ -51,7 +51,8 @@ def _load():
         build()
         lib = ctypes.CDLL(_LIB)
         p = ctypes.c_void_p
-        for name in ("oracle_conv2d_fwd", "oracle_conv2d_dgrad", "oracle_conv2d_wgrad"):
+        for name in ("oracle_conv2d_fwd", "oracle_conv2d_dgrad", "oracle_conv2d_wgrad",
+                     "oracle_conv2d_fwd_f32", "oracle_conv2d_dgrad_f32", "oracle_conv2d_wgrad_f32"):
             fn = getattr(lib, name)
             fn.argtypes = [ctypes.POINTER(ConvDesc), p, p, p, ctypes.c_int64, p]
             fn.restype = ctypes.c_int
@@ -130,6 +131,34 @@ def conv2d_wgrad(d: ConvDesc, x: np.ndarray, dy: np.ndarray, idx=None) -> np.nda
     xb = _half_bits(x, (d.N, d.H, d.W, d.C))
     gb = _half_bits(dy, (d.N, ho, wo, d.K))
     return _run(_load().oracle_conv2d_wgrad, d, xb, gb, (d.K, d.R, d.S, d.C), idx)
+
+
+def _f32(a: np.ndarray, shape: Sequence[int]) -> np.ndarray:
+    a = np.ascontiguousarray(a)
+    if a.dtype != np.float32:
+        raise TypeError("inputs of the single-precision path are binary32 arrays")
+    if tuple(a.shape) != tuple(shape):
+        raise ValueError(f"expected shape {tuple(shape)}, got {a.shape}")
+    return a
+
+
+def conv2d_fwd_f32(d: ConvDesc, x: np.ndarray, w: np.ndarray, idx=None) -> np.ndarray:
+    """conv2d_fwd on binary32 inputs (the full-precision training section 2.2 compares against)."""
+    ho, wo = out_shape(d)
+    return _run(_load().oracle_conv2d_fwd_f32, d, _f32(x, (d.N, d.H, d.W, d.C)), _f32(w, (d.K, d.R, d.S, d.C)),
+                (d.N, ho, wo, d.K), idx)
+
+
+def conv2d_dgrad_f32(d: ConvDesc, dy: np.ndarray, w: np.ndarray, idx=None) -> np.ndarray:
+    ho, wo = out_shape(d)
+    return _run(_load().oracle_conv2d_dgrad_f32, d, _f32(dy, (d.N, ho, wo, d.K)), _f32(w, (d.K, d.R, d.S, d.C)),
+                (d.N, d.H, d.W, d.C), idx)
+
+
+def conv2d_wgrad_f32(d: ConvDesc, x: np.ndarray, dy: np.ndarray, idx=None) -> np.ndarray:
+    ho, wo = out_shape(d)
+    return _run(_load().oracle_conv2d_wgrad_f32, d, _f32(x, (d.N, d.H, d.W, d.C)), _f32(dy, (d.N, ho, wo, d.K)),
+                (d.K, d.R, d.S, d.C), idx)
 
 
 def unscale_check(g: np.ndarray, inv_scale: float):

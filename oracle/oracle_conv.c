@@ -10,6 +10,8 @@
  * bit patterns (the half-precision compute of the paper's "Mixed Precision
  * Training" subsection, section 2.2), and the loss-scale removal with overflow
  * detection that the loss-scaling recipe adopted in that subsection needs.
+ * The *_f32 entry points evaluate the same sums on binary32 inputs (the full-precision
+ * training that subsection compares against).
  * Nothing is blocked, fused or reordered: every output element is one plain
  * nested sum, so the code can be compared with the formulas by eye.
  *
@@ -60,6 +62,15 @@ static double *widen(const uint16_t *src, size_t n)
     double *dst = (double *)malloc((n ? n : 1) * sizeof(double));
     if (!dst) return NULL;
     for (size_t i = 0; i < n; ++i) dst[i] = half_bits_to_double(src[i]);
+    return dst;
+}
+
+/* binary32 -> double is exact as well (the single-precision companion path) */
+static double *widen_f32(const float *src, size_t n)
+{
+    double *dst = (double *)malloc((n ? n : 1) * sizeof(double));
+    if (!dst) return NULL;
+    for (size_t i = 0; i < n; ++i) dst[i] = (double)src[i];
     return dst;
 }
 
@@ -159,12 +170,12 @@ static double wgrad_element(const oracle_conv_desc *d, const double *x, const do
 static size_t numel_x(const oracle_conv_desc *d) { return (size_t)d->N * d->H * d->W * d->C; }
 static size_t numel_w(const oracle_conv_desc *d) { return (size_t)d->K * d->R * d->S * d->C; }
 
-int oracle_conv2d_fwd(const oracle_conv_desc *d, const uint16_t *x16, const uint16_t *w16,
-                      const int64_t *idx, int64_t nidx, double *out)
+/* The three passes on widened (fp64) copies of the inputs; x, w, dy are freed here. */
+static int fwd_widened(const oracle_conv_desc *d, double *x, double *w, const int64_t *idx, int64_t nidx,
+                       double *out)
 {
     int32_t Ho, Wo;
-    if (oracle_conv2d_out_shape(d, &Ho, &Wo) || !x16 || !w16 || !out) return -1;
-    double *x = widen(x16, numel_x(d)), *w = widen(w16, numel_w(d));
+    if (oracle_conv2d_out_shape(d, &Ho, &Wo)) { free(x); free(w); return -1; }
     if (!x || !w) { free(x); free(w); return -2; }
     int64_t total = (int64_t)d->N * Ho * Wo * d->K;
     int64_t count = idx ? nidx : total;
@@ -182,12 +193,27 @@ int oracle_conv2d_fwd(const oracle_conv_desc *d, const uint16_t *x16, const uint
     return 0;
 }
 
-int oracle_conv2d_dgrad(const oracle_conv_desc *d, const uint16_t *dy16, const uint16_t *w16,
-                        const int64_t *idx, int64_t nidx, double *out)
+int oracle_conv2d_fwd(const oracle_conv_desc *d, const uint16_t *x16, const uint16_t *w16,
+                      const int64_t *idx, int64_t nidx, double *out)
 {
     int32_t Ho, Wo;
-    if (oracle_conv2d_out_shape(d, &Ho, &Wo) || !dy16 || !w16 || !out) return -1;
-    double *dy = widen(dy16, (size_t)d->N * Ho * Wo * d->K), *w = widen(w16, numel_w(d));
+    if (oracle_conv2d_out_shape(d, &Ho, &Wo) || !x16 || !w16 || !out) return -1;
+    return fwd_widened(d, widen(x16, numel_x(d)), widen(w16, numel_w(d)), idx, nidx, out);
+}
+
+int oracle_conv2d_fwd_f32(const oracle_conv_desc *d, const float *x32, const float *w32,
+                          const int64_t *idx, int64_t nidx, double *out)
+{
+    int32_t Ho, Wo;
+    if (oracle_conv2d_out_shape(d, &Ho, &Wo) || !x32 || !w32 || !out) return -1;
+    return fwd_widened(d, widen_f32(x32, numel_x(d)), widen_f32(w32, numel_w(d)), idx, nidx, out);
+}
+
+static int dgrad_widened(const oracle_conv_desc *d, double *dy, double *w, const int64_t *idx, int64_t nidx,
+                         double *out)
+{
+    int32_t Ho, Wo;
+    if (oracle_conv2d_out_shape(d, &Ho, &Wo)) { free(dy); free(w); return -1; }
     if (!dy || !w) { free(dy); free(w); return -2; }
     int64_t total = (int64_t)numel_x(d);
     int64_t count = idx ? nidx : total;
@@ -205,12 +231,28 @@ int oracle_conv2d_dgrad(const oracle_conv_desc *d, const uint16_t *dy16, const u
     return 0;
 }
 
-int oracle_conv2d_wgrad(const oracle_conv_desc *d, const uint16_t *x16, const uint16_t *dy16,
+int oracle_conv2d_dgrad(const oracle_conv_desc *d, const uint16_t *dy16, const uint16_t *w16,
                         const int64_t *idx, int64_t nidx, double *out)
 {
     int32_t Ho, Wo;
-    if (oracle_conv2d_out_shape(d, &Ho, &Wo) || !x16 || !dy16 || !out) return -1;
-    double *x = widen(x16, numel_x(d)), *dy = widen(dy16, (size_t)d->N * Ho * Wo * d->K);
+    if (oracle_conv2d_out_shape(d, &Ho, &Wo) || !dy16 || !w16 || !out) return -1;
+    return dgrad_widened(d, widen(dy16, (size_t)d->N * Ho * Wo * d->K), widen(w16, numel_w(d)), idx, nidx, out);
+}
+
+int oracle_conv2d_dgrad_f32(const oracle_conv_desc *d, const float *dy32, const float *w32,
+                            const int64_t *idx, int64_t nidx, double *out)
+{
+    int32_t Ho, Wo;
+    if (oracle_conv2d_out_shape(d, &Ho, &Wo) || !dy32 || !w32 || !out) return -1;
+    return dgrad_widened(d, widen_f32(dy32, (size_t)d->N * Ho * Wo * d->K), widen_f32(w32, numel_w(d)), idx, nidx,
+                         out);
+}
+
+static int wgrad_widened(const oracle_conv_desc *d, double *x, double *dy, const int64_t *idx, int64_t nidx,
+                         double *out)
+{
+    int32_t Ho, Wo;
+    if (oracle_conv2d_out_shape(d, &Ho, &Wo)) { free(x); free(dy); return -1; }
     if (!x || !dy) { free(x); free(dy); return -2; }
     int64_t total = (int64_t)numel_w(d);
     int64_t count = idx ? nidx : total;
@@ -226,6 +268,23 @@ int oracle_conv2d_wgrad(const oracle_conv_desc *d, const uint16_t *x16, const ui
     }
     free(x); free(dy);
     return 0;
+}
+
+int oracle_conv2d_wgrad(const oracle_conv_desc *d, const uint16_t *x16, const uint16_t *dy16,
+                        const int64_t *idx, int64_t nidx, double *out)
+{
+    int32_t Ho, Wo;
+    if (oracle_conv2d_out_shape(d, &Ho, &Wo) || !x16 || !dy16 || !out) return -1;
+    return wgrad_widened(d, widen(x16, numel_x(d)), widen(dy16, (size_t)d->N * Ho * Wo * d->K), idx, nidx, out);
+}
+
+int oracle_conv2d_wgrad_f32(const oracle_conv_desc *d, const float *x32, const float *dy32,
+                            const int64_t *idx, int64_t nidx, double *out)
+{
+    int32_t Ho, Wo;
+    if (oracle_conv2d_out_shape(d, &Ho, &Wo) || !x32 || !dy32 || !out) return -1;
+    return wgrad_widened(d, widen_f32(x32, numel_x(d)), widen_f32(dy32, (size_t)d->N * Ho * Wo * d->K), idx, nidx,
+                         out);
 }
 
 /* ---- loss-scale removal and overflow detection ---------------------------------- */
