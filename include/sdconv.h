@@ -51,7 +51,7 @@ typedef struct {
 enum {
     SDCONV_OK = 0,
     SDCONV_EINVAL = -1,       /* null pointer, non-positive size, empty output, bad scale, misalignment */
-    SDCONV_EUNSUPPORTED = -2, /* reserved: every valid descriptor is supported                          */
+    SDCONV_EUNSUPPORTED = -2, /* the *_f32 calls only: C or K not a multiple of 4, more than 64 taps    */
     SDCONV_EWORKSPACE = -3,   /* workspace missing or smaller than conv2d_workspace_bytes()             */
     SDCONV_EHIP = -4          /* a HIP call failed; see sdconv_last_hip_error()                         */
 };
@@ -177,6 +177,22 @@ typedef struct {
 int conv2d_dgrad_fused(const conv2d_desc *desc, const void *dy, const void *w,
                        const conv2d_dgrad_epilogue *ep, void *dx, void *workspace,
                        size_t workspace_bytes, void *hip_stream);
+
+/* ---- single-precision companion path ----------------------------------------------------------
+ * Section 2.2 and Figure 1(b) of the paper compare mixed-precision training with full-precision
+ * (FP32) training.  These calls run the same three passes on binary32 tensors (binary32
+ * products and accumulation on the fp32 matrix instructions, results binary32), so that the
+ * comparison can be made on this hardware; they are a measurement companion, not a tuned path.
+ * Layouts, conventions, alignment, ownership, asynchrony and error rules are those of the
+ * half-precision calls with every tensor binary32.  Supported: C and K multiples of 4, at most
+ * 64 filter taps, stride_h * stride_w <= 16; other descriptors return SDCONV_EUNSUPPORTED. */
+size_t conv2d_workspace_bytes_f32(const conv2d_desc *desc, int pass);
+int conv2d_fwd_f32(const conv2d_desc *desc, const float *x, const float *w, float *y,
+                   void *workspace, size_t workspace_bytes, void *hip_stream);
+int conv2d_dgrad_f32(const conv2d_desc *desc, const float *dy, const float *w, float *dx,
+                     void *workspace, size_t workspace_bytes, void *hip_stream);
+int conv2d_wgrad_f32(const conv2d_desc *desc, const float *x, const float *dy, float *dw,
+                     void *workspace, size_t workspace_bytes, void *hip_stream);
 
 /* Static, human-readable text for a status code. */
 const char *sdconv_status_string(int status);

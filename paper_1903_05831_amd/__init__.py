@@ -23,6 +23,7 @@ EXPORTS = (
     "grad_unscale_check", "sdconv_status_string", "sdconv_last_hip_error", "sdconv_kernel_name",
     "sdconv_mfma_ceiling", "grad_unscale_check_dynamic", "sgd_momentum_update",
     "conv2d_fwd_fused", "conv2d_dgrad_fused", "sdconv_tail_pass",
+    "conv2d_workspace_bytes_f32", "conv2d_fwd_f32", "conv2d_dgrad_f32", "conv2d_wgrad_f32",
 )
 
 
@@ -85,6 +86,12 @@ def lib() -> ctypes.CDLL:
         L.conv2d_fwd_fused.restype = ctypes.c_int
         L.conv2d_dgrad_fused.argtypes = [dp, vp, vp, ctypes.POINTER(conv2d_dgrad_epilogue), vp, vp, sz, vp]
         L.conv2d_dgrad_fused.restype = ctypes.c_int
+        L.conv2d_workspace_bytes_f32.argtypes = [dp, ctypes.c_int]
+        L.conv2d_workspace_bytes_f32.restype = sz
+        for name in ("conv2d_fwd_f32", "conv2d_dgrad_f32", "conv2d_wgrad_f32"):
+            fn = getattr(L, name)
+            fn.argtypes = [dp, vp, vp, vp, vp, sz, vp]
+            fn.restype = ctypes.c_int
         L.sdconv_tail_pass.argtypes = [vp, sz, ctypes.c_int32, vp, vp, vp, vp, ctypes.c_int32, vp]
         L.sdconv_tail_pass.restype = ctypes.c_int
         L.sdconv_mfma_ceiling.argtypes = [vp, ctypes.c_int, ctypes.c_int, vp]
@@ -177,6 +184,23 @@ def conv2d_dgrad_fused(desc, dy, w, dx, workspace=None, stream: int = 0, *, scal
                                   stream or 0)
     if rc:
         raise SdconvError(rc, "conv2d_dgrad_fused")
+
+
+def conv2d_workspace_bytes_f32(desc: conv2d_desc, pass_id: int) -> int:
+    return int(lib().conv2d_workspace_bytes_f32(ctypes.byref(desc), pass_id))
+
+
+def conv2d_fwd_f32(desc, x, w, y, workspace=None, stream: int = 0) -> None:
+    """Single-precision companion of conv2d_fwd: every tensor fp32."""
+    _call("conv2d_fwd_f32", desc, x, w, y, workspace, stream)
+
+
+def conv2d_dgrad_f32(desc, dy, w, dx, workspace=None, stream: int = 0) -> None:
+    _call("conv2d_dgrad_f32", desc, dy, w, dx, workspace, stream)
+
+
+def conv2d_wgrad_f32(desc, x, dy, dw, workspace=None, stream: int = 0) -> None:
+    _call("conv2d_wgrad_f32", desc, x, dy, dw, workspace, stream)
 
 
 def sdconv_tail_pass(t, pixels: int, channels: int, stream: int = 0, *, scale=None, bias=None, residual=None,

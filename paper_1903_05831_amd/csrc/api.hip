@@ -145,6 +145,52 @@ extern "C" __attribute__((visibility("default"))) int conv2d_wgrad(const conv2d_
                                 (hipStream_t)hip_stream));
 }
 
+extern "C" __attribute__((visibility("default"))) size_t conv2d_workspace_bytes_f32(const conv2d_desc* desc, int pass)
+{
+    int Ho, Wo;
+    if (!desc_shape(desc, &Ho, &Wo)) return 0;
+    return f32_workspace_bytes(make_geom(*desc, Ho, Wo), pass);
+}
+
+static int f32_call(const conv2d_desc* desc, int pass, const float* a, const float* b, float* out, void* workspace,
+                    size_t workspace_bytes, void* hip_stream)
+{
+    int Ho, Wo;
+    if (!desc_shape(desc, &Ho, &Wo)) return SDCONV_EINVAL;
+    Geom g = make_geom(*desc, Ho, Wo);
+    if (!f32_supported(g)) return SDCONV_EUNSUPPORTED;
+    // 32-bit element offsets inside the kernels
+    const size_t lim = (size_t)1 << 31;
+    if ((size_t)g.N * g.H * g.W * g.C >= lim || (size_t)g.N * Ho * Wo * g.K >= lim) return SDCONV_EINVAL;
+    int rc = check_common(desc, a, b, out, workspace, workspace_bytes, f32_workspace_bytes(g, pass), &Ho, &Wo);
+    if (rc) return rc;
+    hipStream_t st = (hipStream_t)hip_stream;
+    if (pass == SDCONV_FWD) return hip_status(run_fwd_f32(g, a, b, out, st));
+    if (pass == SDCONV_DGRAD) return hip_status(run_dgrad_f32(g, a, b, out, workspace, st));
+    return hip_status(run_wgrad_f32(g, a, b, out, workspace, st));
+}
+
+extern "C" __attribute__((visibility("default"))) int conv2d_fwd_f32(const conv2d_desc* desc, const float* x, const float* w,
+                                                                     float* y, void* workspace, size_t workspace_bytes,
+                                                                     void* hip_stream)
+{
+    return f32_call(desc, SDCONV_FWD, x, w, y, workspace, workspace_bytes, hip_stream);
+}
+
+extern "C" __attribute__((visibility("default"))) int conv2d_dgrad_f32(const conv2d_desc* desc, const float* dy,
+                                                                       const float* w, float* dx, void* workspace,
+                                                                       size_t workspace_bytes, void* hip_stream)
+{
+    return f32_call(desc, SDCONV_DGRAD, dy, w, dx, workspace, workspace_bytes, hip_stream);
+}
+
+extern "C" __attribute__((visibility("default"))) int conv2d_wgrad_f32(const conv2d_desc* desc, const float* x,
+                                                                       const float* dy, float* dw, void* workspace,
+                                                                       size_t workspace_bytes, void* hip_stream)
+{
+    return f32_call(desc, SDCONV_WGRAD, x, dy, dw, workspace, workspace_bytes, hip_stream);
+}
+
 extern "C" __attribute__((visibility("default"))) int grad_unscale_check(float* grad, size_t n, float inv_scale, int32_t* found_nonfinite,
                                   void* hip_stream)
 {

@@ -69,6 +69,13 @@ hipError_t run_dgrad(const Geom& g, const Plan& p, const __half* dy, const __hal
                      const Epilogue& ep = no_epilogue());
 hipError_t run_wgrad(const Geom& g, const Plan& p, const __half* x, const __half* dy, float* dw, void* ws, hipStream_t st);
 
+// Single-precision companion path (conv_f32.hip): channel and filter counts in multiples of 4.
+bool f32_supported(const Geom& g);
+size_t f32_workspace_bytes(const Geom& g, int pass);
+hipError_t run_fwd_f32(const Geom& g, const float* x, const float* w, float* y, hipStream_t st);
+hipError_t run_dgrad_f32(const Geom& g, const float* dy, const float* w, float* dx, void* ws, hipStream_t st);
+hipError_t run_wgrad_f32(const Geom& g, const float* x, const float* dy, float* dw, void* ws, hipStream_t st);
+
 // Launchers return hipGetLastError() of their launches.  All work goes to `st`.
 hipError_t launch_direct_fwd(const Geom& g, const __half* x, const __half* w, __half* y, hipStream_t st,
                              const Epilogue& ep = no_epilogue());
