@@ -41,6 +41,9 @@ def main() -> int:
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--streams", type=int, default=2, choices=(1, 2),
                     help="2: weight gradients on a second stream, overlapping the data gradients")
+    ap.add_argument("--core-only", action="store_true",
+                    help="only the timed step and its per-kernel pass (for profiler runs): skip the fused-epilogue, "
+                         "second-workload and FP32 sections, whose launches would mix into the kernel statistics")
     ap.add_argument("--detail", type=str, default="", help="write per-layer timings (JSON) to this file")
     ap.add_argument("--calib-copy-mib", type=int, default=0,
                     help="run one plain streaming kernel over this many MiB first (a known-size reference "
@@ -274,91 +277,118 @@ def main() -> int:
     torch.cuda.synchronize()
     tail_ms = e0.elapsed_time(e1) / 5
     del mw, mbuf, w16
-    # ---- fused epilogues: forward and data-gradient chains of the whole network, one stream -----
-    # every layer gets the tail it has in a residual network with frozen batch normalisation:
-    # affine + ReLU (stem, a, b), affine + shortcut + ReLU (c), affine only (projection p); the
-    # data gradients get the scale and ReLU mask of the activation that feeds the layer.
-    # Three ways: the plain pass, the fused call, the plain pass followed by a separate tail pass.
-    def tail_of(l):
-        if l.name.endswith("c"):
-            return dict(residual=True, relu=True)
-        if l.name.endswith("p"):
-            return dict(residual=False, relu=False)
-        return dict(residual=False, relu=True)
-    vecs = {}
-    for (l, d, x, w, g, y, dx, dw) in jobs:
-        for n in (l.K, l.C):
-            if n not in vecs and n % 8 == 0:
-                vecs[n] = (torch.rand(n, device=dev) + 0.5, torch.randn(n, device=dev))
-    fwd_modes = {"plain": [], "fused": [], "separate": []}
-    dg_modes = {"plain": [], "fused": [], "separate": []}
+    fused_ms = second = None
+    second_ms = second_flops = f32_ms = f16_ms = f32_flops = 0
     tail_bytes_fwd = tail_bytes_dg = 0
-    for (l, d, x, w, g, y, dx, dw) in jobs:
-        t = tail_of(l)
-        sc, bi = vecs[l.K]
-        res = g if t["residual"] else None          # a tensor of y's shape stands in for the shortcut
-        npix = l.N * l.Ho * l.Wo
-        fwd_modes["plain"].append(lambda d=d, x=x, w=w, y=y: sd.conv2d_fwd(d, x, w, y, ws, stream))
-        fwd_modes["fused"].append(lambda d=d, x=x, w=w, y=y, sc=sc, bi=bi, res=res, r=t["relu"]:
-                                  sd.conv2d_fwd_fused(d, x, w, y, ws, stream, scale=sc, bias=bi, residual=res, relu=r))
-        fwd_modes["separate"].append(lambda d=d, x=x, w=w, y=y, sc=sc, bi=bi, res=res, r=t["relu"], npix=npix, K=l.K:
-                                     (sd.conv2d_fwd(d, x, w, y, ws, stream),
-                                      sd.sdconv_tail_pass(y, npix, K, stream, scale=sc, bias=bi, residual=res, relu=r)))
-        tail_bytes_fwd += 2 * y.numel() * (3 if t["residual"] else 2)
-        if l.C % 8:
-            continue                                 # the stem: no gradient with respect to the image
-        scc = vecs[l.C][0]
-        nin = l.N * l.H * l.W
-        dg_modes["plain"].append(lambda d=d, g=g, w=w, dx=dx: sd.conv2d_dgrad(d, g, w, dx, ws, stream))
-        dg_modes["fused"].append(lambda d=d, g=g, w=w, dx=dx, scc=scc, x=x:
-                                 sd.conv2d_dgrad_fused(d, g, w, dx, ws, stream, scale=scc, relu_mask=x))
-        dg_modes["separate"].append(lambda d=d, g=g, w=w, dx=dx, scc=scc, x=x, nin=nin, C=l.C:
-                                    (sd.conv2d_dgrad(d, g, w, dx, ws, stream),
-                                     sd.sdconv_tail_pass(dx, nin, C, stream, scale=scc, relu_mask=x)))
-        tail_bytes_dg += 2 * dx.numel() * 3
+    if not args.core_only:
+        # ---- fused epilogues: forward and data-gradient chains of the whole network, one stream -----
+        # every layer gets the tail it has in a residual network with frozen batch normalisation:
+        # affine + ReLU (stem, a, b), affine + shortcut + ReLU (c), affine only (projection p); the
+        # data gradients get the scale and ReLU mask of the activation that feeds the layer.
+        # Three ways: the plain pass, the fused call, the plain pass followed by a separate tail pass.
+        def tail_of(l):
+            if l.name.endswith("c"):
+                return dict(residual=True, relu=True)
+            if l.name.endswith("p"):
+                return dict(residual=False, relu=False)
+            return dict(residual=False, relu=True)
+        vecs = {}
+        for (l, d, x, w, g, y, dx, dw) in jobs:
+            for n in (l.K, l.C):
+                if n not in vecs and n % 8 == 0:
+                    vecs[n] = (torch.rand(n, device=dev) + 0.5, torch.randn(n, device=dev))
+        fwd_modes = {"plain": [], "fused": [], "separate": []}
+        dg_modes = {"plain": [], "fused": [], "separate": []}
+        tail_bytes_fwd = tail_bytes_dg = 0
+        for (l, d, x, w, g, y, dx, dw) in jobs:
+            t = tail_of(l)
+            sc, bi = vecs[l.K]
+            res = g if t["residual"] else None          # a tensor of y's shape stands in for the shortcut
+            npix = l.N * l.Ho * l.Wo
+            fwd_modes["plain"].append(lambda d=d, x=x, w=w, y=y: sd.conv2d_fwd(d, x, w, y, ws, stream))
+            fwd_modes["fused"].append(lambda d=d, x=x, w=w, y=y, sc=sc, bi=bi, res=res, r=t["relu"]:
+                                      sd.conv2d_fwd_fused(d, x, w, y, ws, stream, scale=sc, bias=bi, residual=res, relu=r))
+            fwd_modes["separate"].append(lambda d=d, x=x, w=w, y=y, sc=sc, bi=bi, res=res, r=t["relu"], npix=npix, K=l.K:
+                                         (sd.conv2d_fwd(d, x, w, y, ws, stream),
+                                          sd.sdconv_tail_pass(y, npix, K, stream, scale=sc, bias=bi, residual=res, relu=r)))
+            tail_bytes_fwd += 2 * y.numel() * (3 if t["residual"] else 2)
+            if l.C % 8:
+                continue                                 # the stem: no gradient with respect to the image
+            scc = vecs[l.C][0]
+            nin = l.N * l.H * l.W
+            dg_modes["plain"].append(lambda d=d, g=g, w=w, dx=dx: sd.conv2d_dgrad(d, g, w, dx, ws, stream))
+            dg_modes["fused"].append(lambda d=d, g=g, w=w, dx=dx, scc=scc, x=x:
+                                     sd.conv2d_dgrad_fused(d, g, w, dx, ws, stream, scale=scc, relu_mask=x))
+            dg_modes["separate"].append(lambda d=d, g=g, w=w, dx=dx, scc=scc, x=x, nin=nin, C=l.C:
+                                        (sd.conv2d_dgrad(d, g, w, dx, ws, stream),
+                                         sd.sdconv_tail_pass(dx, nin, C, stream, scale=scc, relu_mask=x)))
+            tail_bytes_dg += 2 * dx.numel() * 3
 
-    def time_chain(fns, reps=3):
-        for f in fns:
-            f()
-        torch.cuda.synchronize()
-        e0.record()
-        for _ in range(reps):
+        def time_chain(fns, reps=3):
             for f in fns:
                 f()
-        e1.record()
-        torch.cuda.synchronize()
-        return e0.elapsed_time(e1) / reps
-    fused_ms = {"fwd": {k: time_chain(v) for k, v in fwd_modes.items()},
-                "dgrad": {k: time_chain(v) for k, v in dg_modes.items()}}
-    # ---- second shape set: what a ResNet-50-FPN Faster R-CNN adds (Table 1 of the paper quotes its
-    # speed on that model): res5 on the image, FPN, RPN heads on P2-P6, box-head FCs, C4 RPN --------
-    del fwd_modes, dg_modes
-    torch.cuda.empty_cache()
-    second = {}
-    fns2, flops2 = {}, {}
-    for l in workloads.CONFIGS[6]:
-        d2 = sd.desc_of(l)
-        x2 = torch.randn(l.x_shape, device=dev, dtype=torch.float32).half()
-        w2 = (torch.randn(l.w_shape, device=dev, dtype=torch.float32) * (2.0 / (l.R * l.S * l.C)) ** 0.5).half()
-        g2 = torch.randn(l.y_shape, device=dev, dtype=torch.float32).half()
-        y2 = torch.empty(l.y_shape, dtype=torch.float16, device=dev)
-        dx2 = torch.empty(l.x_shape, dtype=torch.float16, device=dev)
-        dw2 = torch.empty(l.w_shape, dtype=torch.float32, device=dev)
-        need = max(sd.conv2d_workspace_bytes(d2, pid) for pid in (sd.FWD, sd.DGRAD, sd.WGRAD))
-        wsl = torch.empty(max(need, 256), dtype=torch.uint8, device=dev)
-        grp = l.name.split(".")[0]
-        fns2.setdefault(grp, []).extend([
-            lambda d2=d2, x2=x2, w2=w2, y2=y2, wsl=wsl: sd.conv2d_fwd(d2, x2, w2, y2, wsl, stream),
-            lambda d2=d2, g2=g2, w2=w2, dx2=dx2, wsl=wsl: sd.conv2d_dgrad(d2, g2, w2, dx2, wsl, stream),
-            lambda d2=d2, x2=x2, g2=g2, dw2=dw2, wsl=wsl: sd.conv2d_wgrad(d2, x2, g2, dw2, wsl, stream)])
-        flops2[grp] = flops2.get(grp, 0) + 3 * l.flops
-    for grp, fns in fns2.items():
-        ms = time_chain(fns)
-        second[grp] = {"ms": ms, "gflop": flops2[grp] / 1e9, "tflops": flops2[grp] / ms / 1e9}
-    second_ms = sum(v["ms"] for v in second.values())
-    second_flops = sum(flops2.values())
-    del fns2
-    torch.cuda.empty_cache()
+            torch.cuda.synchronize()
+            e0.record()
+            for _ in range(reps):
+                for f in fns:
+                    f()
+            e1.record()
+            torch.cuda.synchronize()
+            return e0.elapsed_time(e1) / reps
+        fused_ms = {"fwd": {k: time_chain(v) for k, v in fwd_modes.items()},
+                    "dgrad": {k: time_chain(v) for k, v in dg_modes.items()}}
+        # ---- second shape set: what a ResNet-50-FPN Faster R-CNN adds (Table 1 of the paper quotes its
+        # speed on that model): res5 on the image, FPN, RPN heads on P2-P6, box-head FCs, C4 RPN --------
+        del fwd_modes, dg_modes
+        torch.cuda.empty_cache()
+        second = {}
+        fns2, flops2 = {}, {}
+        for l in workloads.CONFIGS[6]:
+            d2 = sd.desc_of(l)
+            x2 = torch.randn(l.x_shape, device=dev, dtype=torch.float32).half()
+            w2 = (torch.randn(l.w_shape, device=dev, dtype=torch.float32) * (2.0 / (l.R * l.S * l.C)) ** 0.5).half()
+            g2 = torch.randn(l.y_shape, device=dev, dtype=torch.float32).half()
+            y2 = torch.empty(l.y_shape, dtype=torch.float16, device=dev)
+            dx2 = torch.empty(l.x_shape, dtype=torch.float16, device=dev)
+            dw2 = torch.empty(l.w_shape, dtype=torch.float32, device=dev)
+            need = max(sd.conv2d_workspace_bytes(d2, pid) for pid in (sd.FWD, sd.DGRAD, sd.WGRAD))
+            wsl = torch.empty(max(need, 256), dtype=torch.uint8, device=dev)
+            grp = l.name.split(".")[0]
+            fns2.setdefault(grp, []).extend([
+                lambda d2=d2, x2=x2, w2=w2, y2=y2, wsl=wsl: sd.conv2d_fwd(d2, x2, w2, y2, wsl, stream),
+                lambda d2=d2, g2=g2, w2=w2, dx2=dx2, wsl=wsl: sd.conv2d_dgrad(d2, g2, w2, dx2, wsl, stream),
+                lambda d2=d2, x2=x2, g2=g2, dw2=dw2, wsl=wsl: sd.conv2d_wgrad(d2, x2, g2, dw2, wsl, stream)])
+            flops2[grp] = flops2.get(grp, 0) + 3 * l.flops
+        for grp, fns in fns2.items():
+            ms = time_chain(fns)
+            second[grp] = {"ms": ms, "gflop": flops2[grp] / 1e9, "tflops": flops2[grp] / ms / 1e9}
+        second_ms = sum(v["ms"] for v in second.values())
+        second_flops = sum(flops2.values())
+        del fns2
+        torch.cuda.empty_cache()
+        # ---- FP32 -> FP16 on this hardware (the form of Figure 1(b) of the paper): the same layers,
+        # all three passes, through the single-precision companion path and through the mixed-
+        # precision path, layer by layer on one stream (the C = 3 stem is left out: the companion
+        # path takes channel counts in multiples of 4) -------------------------------------------------
+        f32_ms = f16_ms = 0.0
+        f32_flops = 0
+        for (l, d, x, w, g, y, dx, dw) in jobs:
+            if l.C % 4 or l.K % 4:
+                continue
+            need = max(sd.conv2d_workspace_bytes_f32(d, pid) for pid in (sd.FWD, sd.DGRAD, sd.WGRAD))
+            ws32 = torch.empty(max(need, 256), dtype=torch.uint8, device=dev)
+            x32, w32, g32 = x.float(), w.float(), g.float()
+            y32, dx32, dw32 = torch.empty_like(g32), torch.empty_like(x32), torch.empty(l.w_shape, dtype=torch.float32, device=dev)
+            f32_ms += time_chain([lambda: sd.conv2d_fwd_f32(d, x32, w32, y32, ws32, stream),
+                                  lambda: sd.conv2d_dgrad_f32(d, g32, w32, dx32, ws32, stream),
+                                  lambda: sd.conv2d_wgrad_f32(d, x32, g32, dw32, ws32, stream)], reps=2)
+            f16_ms += time_chain([lambda: sd.conv2d_fwd(d, x, w, y, ws, stream),
+                                  lambda: sd.conv2d_dgrad(d, g, w, dx, ws, stream),
+                                  lambda: sd.conv2d_wgrad(d, x, g, dw, ws, stream)], reps=2)
+            f32_flops += 3 * l.flops
+            del x32, w32, g32, y32, dx32, dw32, ws32
+        torch.cuda.empty_cache()
+
     # what the matrix pipes sustain with nothing else in the way (see sdconv_mfma_ceiling)
     props = torch.cuda.get_device_properties(dev)
     cus = props.multi_processor_count
@@ -401,17 +431,24 @@ def main() -> int:
                            "us": tail_ms * 1e3, "bytes": 30 * dw_total,
                            "GBps": 30.0 * dw_total / tail_ms / 1e6,
                            "frac_hbm": 30.0 * dw_total / tail_ms / 1e6 / PEAK_HBM_GBS},
-        "fused_epilogue": {
+        "fused_epilogue": None if args.core_only else {
             "what": "forward / data-gradient chains of all layers on one stream: plain pass, fused tail "
                     "(frozen-BN affine, shortcut on the c layers, ReLU; scale + ReLU mask in the data gradient), "
                     "plain pass + separate in-place tail pass",
             "fwd_ms": fused_ms["fwd"], "dgrad_ms": fused_ms["dgrad"],
             "separate_pass_algorithmic_bytes": {"fwd": tail_bytes_fwd, "dgrad": tail_bytes_dg}},
-        "second_workload": {
+        "second_workload": None if args.core_only else {
             "workload": "config 6: " + workloads.CONFIG_NAMES[6],
             "what": "fwd + dgrad + wgrad of each layer, one stream, per group of layers",
             "layers": len(workloads.CONFIGS[6]), "ms": second_ms, "gflop": second_flops / 1e9,
             "tflops": second_flops / second_ms / 1e9, "groups": second},
+        "fp32_vs_fp16": None if args.core_only else {
+            "what": "fwd + dgrad + wgrad of the 52 layers after the stem, layer by layer on one stream: "
+                    "conv2d_*_f32 (fp32 MFMA) against conv2d_* (fp16 MFMA, fp32 accumulation)",
+            "fp32_ms": f32_ms, "fp16_ms": f16_ms, "speedup": f32_ms / f16_ms,
+            "fp32_tflops": f32_flops / f32_ms / 1e9, "fp32_frac_of_peak": f32_flops / f32_ms / 1e9 / 157.3,
+            "fp16_tflops": f32_flops / f16_ms / 1e9,
+            "paper": "Fig. 1(b): 2.0x end to end (whole training step, hardware not stated)"},
         "device": {"name": props.name, "compute_units": cus, "mfma_only_tflops": ceiling_tflops, "mfma_only_frac_of_peak": ceiling_tflops / PEAK_F16_TFLOPS},
         "ms_per_step_with_events": instrumented_ms,
         "one_stream_events": {"tflops": flops_per_step / instrumented_ms / 1e9,
