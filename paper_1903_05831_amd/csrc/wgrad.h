@@ -15,6 +15,7 @@ struct WgradParams {
     int splits;         // pixel ranges
     int steps_per_split;  // 64-pixel steps each split covers
     int tiles_k, tiles_c; // filter tiles, channel tiles (per tap)
+    int total_blocks;     // tiles_c * tiles_k * R * S * splits (set by the launcher)
 };
 
 struct WgradVariant { int bm, bn; const char* name; };

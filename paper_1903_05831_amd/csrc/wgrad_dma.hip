@@ -66,7 +66,14 @@ __global__ __launch_bounds__(64 * WGM * WGN) void wgrad_dma_kernel(WgradParams P
     const bool fetcher = wave >= FW0;
     const int ft = tid - FW0 * 64, fw = wave - FW0;         // index among the fetching threads / waves
 
-    int b = blockIdx.x;
+    // Which tile: the tiles of one pixel range (all filter tiles, channel tiles and taps of a
+    // split) read the same dy and x rows, and each XCD has an L2 of its own, so runs of 8
+    // consecutive tiles go to one XCD (workgroup b runs on XCD b % 8) instead of being dealt round
+    // over all eight, which made every XCD fetch every operand row again.
+    constexpr int kRun = 8;
+    const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
+    int b = ((slot / kRun) * 8 + xcd) * kRun + (slot % kRun);
+    if (b >= P.total_blocks) return;
     const int tc = b % P.tiles_c; b /= P.tiles_c;
     const int tk = b % P.tiles_k; b /= P.tiles_k;
     const int tap = b % (P.R * P.S);
@@ -227,11 +234,11 @@ __global__ __launch_bounds__(64 * WGM * WGN) void wgrad_dma_kernel(WgradParams P
 }
 
 template <int BM, int BN, int WGM, int WGN, int S, int BP, bool HF = false, int MF = 32>
-static hipError_t launch_wdma(const WgradParams& P, hipStream_t st)
+static hipError_t launch_wdma(const WgradParams& P0, hipStream_t st)
 {
     constexpr size_t lds = (size_t)S * BP * (BM + BN) * 2 + (size_t)S * BP * sizeof(unsigned);
     static_assert(lds <= 160 * 1024, "LDS budget");
-    const bool linear = P.R == 1 && P.S == 1 && P.sh == 1 && P.sw == 1 && P.ph == 0 && P.pw == 0;
+    const bool linear = P0.R == 1 && P0.S == 1 && P0.sh == 1 && P0.sw == 1 && P0.ph == 0 && P0.pw == 0;
     static bool configured = false;
     if (!configured) {
         hipError_t e = hipFuncSetAttribute(
@@ -244,7 +251,9 @@ static hipError_t launch_wdma(const WgradParams& P, hipStream_t st)
         if (e != hipSuccess) return e;
         configured = true;
     }
-    long blocks = (long)P.tiles_c * P.tiles_k * P.R * P.S * P.splits;
+    WgradParams P = P0;
+    P.total_blocks = P.tiles_c * P.tiles_k * P.R * P.S * P.splits;
+    const long blocks = ((long)P.total_blocks + 63) / 64 * 64;     // whole runs of 8 tiles on each of 8 XCDs
     if (linear)
         hipLaunchKernelGGL((wgrad_dma_kernel<BM, BN, WGM, WGN, S, BP, true, HF, MF>), dim3((unsigned)blocks),
                            dim3(64 * WGM * WGN), lds, st, P);
