@@ -465,28 +465,37 @@ static hipError_t run_f32_igemm(const Geom& g, bool dgrad, const float* A, const
     P.sh = g.sh; P.sw = g.sw; P.ph = g.ph; P.pw = g.pw; P.dh = g.dh; P.dw = g.dw;
     P.sw_cls = dgrad ? g.sw : 1;
     P.b_row_pitch = g.R * g.S * P.Cs;
-    const int bm = 128, bn = P.Cd <= 64 ? 64 : 128;
-    int acc = 0;
-    if (!dgrad) {
-        P.nclasses = 1;
-        P.class_tile_start[0] = 0;
-        acc = (int)(((long)g.N * g.Ho * g.Wo + bm - 1) / bm);
-        P.class_tile_start[1] = acc;
-    } else {
-        P.nclasses = g.sh * g.sw;
-        for (int q = 0; q < P.nclasses; ++q) {
-            int a = q / g.sw, b = q % g.sw;
-            long Hi = (g.H - a + g.sh - 1) / g.sh, Wj = (g.W - b + g.sw - 1) / g.sw;
-            if (Hi < 0) Hi = 0;
-            if (Wj < 0) Wj = 0;
-            P.class_tile_start[q] = acc;
-            acc += (int)((g.N * Hi * Wj + bm - 1) / bm);
+    // Tile: the largest of 128x128, 128x64, 64x64 that still gives two workgroups to every compute
+    // unit (these kernels are matrix-bound, so an idle compute unit costs its full share), else
+    // the smallest.
+    auto count_tiles = [&](int bm, int bn, bool fill) {
+        int acc = 0;
+        if (!dgrad) {
+            if (fill) { P.nclasses = 1; P.class_tile_start[0] = 0; }
+            acc = (int)(((long)g.N * g.Ho * g.Wo + bm - 1) / bm);
+            if (fill) P.class_tile_start[1] = acc;
+        } else {
+            const int nc = g.sh * g.sw;
+            if (fill) P.nclasses = nc;
+            for (int q = 0; q < nc; ++q) {
+                int a = q / g.sw, b = q % g.sw;
+                long Hi = (g.H - a + g.sh - 1) / g.sh, Wj = (g.W - b + g.sw - 1) / g.sw;
+                if (Hi < 0) Hi = 0;
+                if (Wj < 0) Wj = 0;
+                if (fill) P.class_tile_start[q] = acc;
+                acc += (int)((g.N * Hi * Wj + bm - 1) / bm);
+            }
+            if (fill) P.class_tile_start[nc] = acc;
         }
-        P.class_tile_start[P.nclasses] = acc;
-    }
+        return (long)acc * ((P.Cd + bn - 1) / bn);
+    };
+    int bm = 64, bn = 64;
+    if (P.Cd > 64 && count_tiles(128, 128, false) >= 512) { bm = 128; bn = 128; }
+    else if (count_tiles(128, 64, false) >= 512) { bm = 128; bn = 64; }
     P.tiles_n = (P.Cd + bn - 1) / bn;
-    P.total_tiles = acc * P.tiles_n;
+    P.total_tiles = (int)count_tiles(bm, bn, true);
     if (P.total_tiles <= 0) return hipErrorInvalidValue;
+    if (bm == 64) return dgrad ? launch_f32_variant<1, 64, 64, 2, 2>(P, st) : launch_f32_variant<0, 64, 64, 2, 2>(P, st);
     if (bn == 64) return dgrad ? launch_f32_variant<1, 128, 64, 2, 2>(P, st) : launch_f32_variant<0, 128, 64, 2, 2>(P, st);
     return dgrad ? launch_f32_variant<1, 128, 128, 2, 2>(P, st) : launch_f32_variant<0, 128, 128, 2, 2>(P, st);
 }
