@@ -121,15 +121,26 @@ static int pick_variant(const Geom& g, bool dgrad)
     if (fv >= 300 && fv < 300 + kNumIgemmWsVariants) return fv;
     if (const TunedEntry* e = tuned_lookup(g, dgrad ? SDCONV_DGRAD : SDCONV_FWD))
         if (e->variant < 400 || patch_variant_ok(g, dgrad, e->variant)) return e->variant;
-    int nout = dgrad ? g.C : g.K;
-    int kgemm = g.R * g.S * (dgrad ? g.K : g.C);
+    // No table entry: rules read off the tuned layers of the detector workloads.
+    const int nout = dgrad ? g.C : g.K;
+    const int kgemm = g.R * g.S * (dgrad ? g.K : g.C);
+    const long rows = dgrad ? (long)g.N * g.H * g.W : (long)g.N * g.Ho * g.Wo;
     int starts[kMaxClasses + 1], nc;
-    // Narrow outputs: 64-wide tiles.  Long contractions with enough rows to fill the chip
-    // with 256x256 tiles: the big tile (half the LDS traffic per flop).  Otherwise 128x128.
+    // stride-1 3x3-class layers: the patch-resident kernel (wide blocks when there is enough work),
+    // unless its 10x14 pixel blocks would be mostly empty (the 7x7 maps of an RoI head)
+    const int Hd = dgrad ? g.H : g.Ho, Wd = dgrad ? g.W : g.Wo;
+    const long covered = (long)((Hd + 9) / 10) * 10 * ((Wd + 13) / 14) * 14;
+    const bool blocks_fill = covered * 2 <= (long)Hd * Wd * 3;      // at most 1.5x the pixels
+    if (blocks_fill && nout >= 128 && rows >= 20000 && patch_variant_ok(g, dgrad, 415)) return 415;
+    if (blocks_fill && patch_variant_ok(g, dgrad, dgrad ? 414 : 419)) return dgrad ? 414 : 419;
+    // narrow outputs: 64-wide tiles
     if (nout <= 64) return 100 + 7;
-    int t256 = row_tiles(g, dgrad, 256, starts, &nc) * ((nout + 255) / 256);
-    if (kgemm >= 2048 && t256 >= 160) return 100 + 8;
-    return 100 + 0;
+    // enough rows to fill the chip with 224-row tiles: the big tile for long contractions and wide
+    // outputs (half the LDS traffic per flop), else the 128-wide one; small layers: 128x128
+    const int t224 = row_tiles(g, dgrad, 224, starts, &nc);
+    if (kgemm >= 512 && nout >= 256 && (long)t224 * ((nout + 255) / 256) >= 200) return 300 + 10;
+    if ((long)t224 * ((nout + 127) / 128) >= 200) return 300 + 16;
+    return 300 + 0;
 }
 
 static bool thin_ok(const Geom& g) { return !force_direct() && g.C <= 4 && thin_supported(g); }
@@ -205,7 +216,15 @@ static int pick_wgrad_variant(const Geom& g)
     int fv = forced_wgrad_variant();
     if ((fv >= 0 && fv < kNumWgradVariants) || (fv >= 100 && fv < 100 + kNumWgradDmaVariants)) return fv;
     if (const TunedEntry* e = tuned_lookup(g, SDCONV_WGRAD)) return e->variant;
-    return (g.K <= 64) ? 1 : 0;
+    // No table entry: rules read off the tuned layers of the detector workloads (tile = filters x
+    // channels of one tap): narrow tiles for narrow layers, the 256x256 tile when both are wide
+    // and the pixel axis is long enough to feed it, else 128x128.
+    const long pixels = (long)g.N * g.Ho * g.Wo;
+    if (g.K <= 64 && g.C <= 64) return 100 + 7;
+    if (g.K <= 64) return 100 + 20;
+    if (g.C <= 64) return 100 + 8;
+    if (g.K >= 512 && g.C >= 512 && pixels >= 20000) return 100 + 14;
+    return 100 + 12;
 }
 
 static void wgrad_split(const Geom& g, int variant, int* splits, int* steps_per_split)
