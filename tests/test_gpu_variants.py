@@ -89,12 +89,27 @@ def test_split_role_kernel_variants(variant):
             check_all_passes(d, x, w, g, f"ws{variant}{case}")
 
 
+# the kernels in which every wave fetches its own share (igemm_dma.hip, 100-111) and the
+# register-staged ones (igemm.hip, 0-3); their data gradient takes a transposed filter copy
+DMA_VARIANTS = [0, 1, 2, 3] + list(range(100, 112))
+
+
+@pytest.mark.parametrize("variant", DMA_VARIANTS)
+def test_all_wave_fetch_kernel_variants(variant):
+    for case in WS_SHAPES:
+        say(f"dma variant {variant} case {case}")
+        d, x, w, g = _rand_case(*case, seed=variant * 19 + 5)
+        with forced(SDCONV_IGEMM_VARIANT=variant, SDCONV_NO_TUNED_TABLE=1):
+            assert "_ws_" not in sd.kernel_name(d, sd.FWD) and "patch" not in sd.kernel_name(d, sd.FWD)
+            check_all_passes(d, x, w, g, f"dma{variant}{case}")
+
+
 WGRAD_SHAPES = [
     (2, 23, 29, 64, 72, 3, 3, (2, 2), (1, 1), (1, 1)),      # strided, gathered x rows, filter tail
     (1, 31, 37, 136, 200, 3, 3, (1, 1), (1, 1), (1, 1)),    # channel and filter tails
     (1, 31, 37, 128, 264, 1, 1, (1, 1), (0, 0), (1, 1)),    # 1x1 unpadded: linear x addressing
 ]
-WGRAD_VARIANTS = list(range(100, 121))
+WGRAD_VARIANTS = [0, 1] + list(range(100, 121))      # 0, 1: the register-staged kernels of wgrad.hip
 
 
 @pytest.mark.parametrize("variant", WGRAD_VARIANTS)
