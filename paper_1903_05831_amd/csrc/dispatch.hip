@@ -150,8 +150,11 @@ static bool thin_ok(const Geom& g) { return !force_direct() && g.C <= 4 && thin_
 // live in the workspace (padk.hip).
 static bool padk_ok(const Geom& g)
 {
-    return !force_direct() && !env_int("SDCONV_NO_PADK", 0) && g.K % 8 != 0 && g.C % 8 == 0 && g.R * g.S <= kMaxTaps &&
-           g.sh * g.sw <= kMaxClasses;
+    if (force_direct() || env_int("SDCONV_NO_PADK", 0)) return false;
+    if (g.K % 8 == 0 || g.C % 8 != 0 || g.R * g.S > kMaxTaps || g.sh * g.sw > kMaxClasses) return false;
+    // the padded copies must stay below 2^31 elements like every other tensor
+    const long kp = (g.K + 7) / 8 * 8, lim = 0x7fffffffL;
+    return (long)g.N * g.Ho * g.Wo * kp <= lim && kp * g.R * g.S * g.C <= lim;
 }
 static Geom padded_k(const Geom& g) { Geom p = g; p.K = (g.K + 7) / 8 * 8; return p; }
 static size_t padk_filter_bytes(const Geom& gp) { return align256((size_t)gp.K * gp.R * gp.S * gp.C * sizeof(__half)); }

@@ -366,6 +366,10 @@ const IgemmVariant kIgemmWsVariants[kNumIgemmWsVariants] = {
     {256, 128, "igemm_fwd_ws_256x128x64_8w0f_s3_m16", "igemm_dgrad_ws_256x128x64_8w0f_s3_m16"},
     {128, 256, "igemm_fwd_ws_128x256x64_8w0f_s3_m16", "igemm_dgrad_ws_128x256x64_8w0f_s3_m16"},
     {224, 128, "igemm_fwd_ws_224x128x64_8w0f_s3_m16", "igemm_dgrad_ws_224x128x64_8w0f_s3_m16"},
+    {64, 64, "igemm_fwd_ws_64x64x64_4w2f_s4", "igemm_dgrad_ws_64x64x64_4w2f_s4"},
+    {64, 128, "igemm_fwd_ws_64x128x64_4w2f_s4", "igemm_dgrad_ws_64x128x64_4w2f_s4"},
+    {64, 64, "igemm_fwd_ws_64x64x64_4w2f_s4_m16", "igemm_dgrad_ws_64x64x64_4w2f_s4_m16"},
+    {64, 128, "igemm_fwd_ws_64x128x64_4w2f_s4_m16", "igemm_dgrad_ws_64x128x64_4w2f_s4_m16"},
 };
 
 #define SDCONV_WS_CASE(idx, BM, BN, WGM, WGN, S, BK, NP)                                      \
@@ -400,6 +404,16 @@ hipError_t launch_igemm_ws(int variant, const IgemmParams& P, hipStream_t st)
         case 31: return launch_ws_variant<1, 128, 256, 2, 4, 3, 64, 0, 16>(P, st);
         case 32: return launch_ws_variant<0, 224, 128, 2, 4, 3, 64, 0, 16>(P, st);
         case 33: return launch_ws_variant<1, 224, 128, 2, 4, 3, 64, 0, 16>(P, st);
+        // small tiles: layers with few pixels (res5 on a 25x42 map, fully connected heads) still
+        // give every compute unit a workgroup
+        case 34: return launch_ws_variant<0, 64, 64, 2, 2, 4, 64, 2>(P, st);
+        case 35: return launch_ws_variant<1, 64, 64, 2, 2, 4, 64, 2>(P, st);
+        case 36: return launch_ws_variant<0, 64, 128, 2, 2, 4, 64, 2>(P, st);
+        case 37: return launch_ws_variant<1, 64, 128, 2, 2, 4, 64, 2>(P, st);
+        case 38: return launch_ws_variant<0, 64, 64, 2, 2, 4, 64, 2, 16>(P, st);
+        case 39: return launch_ws_variant<1, 64, 64, 2, 2, 4, 64, 2, 16>(P, st);
+        case 40: return launch_ws_variant<0, 64, 128, 2, 2, 4, 64, 2, 16>(P, st);
+        case 41: return launch_ws_variant<1, 64, 128, 2, 2, 4, 64, 2, 16>(P, st);
         default: return hipErrorInvalidValue;
     }
 }
