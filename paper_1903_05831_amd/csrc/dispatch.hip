@@ -140,6 +140,13 @@ static int pick_variant(const Geom& g, bool dgrad)
     const int t224 = row_tiles(g, dgrad, 224, starts, &nc);
     if (kgemm >= 512 && nout >= 256 && (long)t224 * ((nout + 255) / 256) >= 200) return 300 + 10;
     if ((long)t224 * ((nout + 127) / 128) >= 200) return 300 + 16;
+    // few pixels (a 25x42 map, a fully connected head): small tiles, so that every compute unit
+    // still gets a workgroup
+    const long t128 = (long)row_tiles(g, dgrad, 128, starts, &nc) * ((nout + 127) / 128);
+    if (t128 < 160) {
+        const long t64x128 = (long)row_tiles(g, dgrad, 64, starts, &nc) * ((nout + 127) / 128);
+        return t64x128 >= 200 ? 300 + 20 : 300 + 19;
+    }
     return 300 + 0;
 }
 
