@@ -417,11 +417,18 @@ static void f32_wgrad_shape(const Geom& g, int* bm, int* bn, int* splits, int* s
     *bn = g.C <= 64 ? 64 : 128;
     const long tiles = (long)((g.K + *bm - 1) / *bm) * ((g.C + *bn - 1) / *bn) * g.R * g.S;
     const long total_steps = ((long)g.N * g.Ho * g.Wo + kF32BP - 1) / kF32BP;
-    long want = (512 + tiles - 1) / tiles;
+    // enough pixel ranges for two workgroups per compute unit, in whole multiples of the unit count
     long cap = total_steps / 8;
     if (cap < 1) cap = 1;
-    if (want > cap) want = cap;
-    if (want < 1) want = 1;
+    long want = 1;
+    double best = -1.0;
+    for (long sp = 1; sp <= cap && sp * tiles <= 2048; ++sp) {
+        const long wgs = sp * tiles;
+        const double fill = (double)wgs / (double)(((wgs + 255) / 256) * 256);
+        const double enough = wgs >= 512 ? 1.0 : (double)wgs / 512.0;
+        const double score = fill * enough - 1e-5 * sp;         // ties: fewer partial sums
+        if (score > best) { best = score; want = sp; }
+    }
     const long per = (total_steps + want - 1) / want;
     *sps = (int)per;
     *splits = (int)((total_steps + per - 1) / per);
@@ -465,9 +472,8 @@ static hipError_t run_f32_igemm(const Geom& g, bool dgrad, const float* A, const
     P.sh = g.sh; P.sw = g.sw; P.ph = g.ph; P.pw = g.pw; P.dh = g.dh; P.dw = g.dw;
     P.sw_cls = dgrad ? g.sw : 1;
     P.b_row_pitch = g.R * g.S * P.Cs;
-    // Tile: the largest of 128x128, 128x64, 64x64 that still gives two workgroups to every compute
-    // unit (these kernels are matrix-bound, so an idle compute unit costs its full share), else
-    // the smallest.
+    // Tile: 128x128, 128x64 or 64x64, chosen below (these kernels are matrix-bound, so an idle or
+    // overloaded compute unit costs its full share).
     auto count_tiles = [&](int bm, int bn, bool fill) {
         int acc = 0;
         if (!dgrad) {
@@ -489,9 +495,19 @@ static hipError_t run_f32_igemm(const Geom& g, bool dgrad, const float* A, const
         }
         return (long)acc * ((P.Cd + bn - 1) / bn);
     };
+    // score = how evenly the tiles spread over the compute units (they are all resident at once and
+    // share the matrix pipes: the fullest unit sets the time) x a small preference for the larger tile
+    const int cus = 256;
+    const int cand[3][2] = {{128, 128}, {128, 64}, {64, 64}};
+    const double pref[3] = {1.0, 0.96, 0.90};
     int bm = 64, bn = 64;
-    if (P.Cd > 64 && count_tiles(128, 128, false) >= 512) { bm = 128; bn = 128; }
-    else if (count_tiles(128, 64, false) >= 512) { bm = 128; bn = 64; }
+    double best = -1.0;
+    for (int i = 0; i < 3; ++i) {
+        if (cand[i][1] == 128 && P.Cd <= 64) continue;
+        const long t = count_tiles(cand[i][0], cand[i][1], false);
+        const double fill = (double)t / (double)(((t + cus - 1) / cus) * cus);
+        if (fill * pref[i] > best) { best = fill * pref[i]; bm = cand[i][0]; bn = cand[i][1]; }
+    }
     P.tiles_n = (P.Cd + bn - 1) / bn;
     P.total_tiles = (int)count_tiles(bm, bn, true);
     if (P.total_tiles <= 0) return hipErrorInvalidValue;
