@@ -34,7 +34,7 @@ extern const IgemmVariant kIgemmVariants[kNumIgemmVariants];
 constexpr int kNumIgemmDmaVariants = 12;
 extern const IgemmVariant kIgemmDmaVariants[kNumIgemmDmaVariants];
 hipError_t launch_igemm_dma(int variant, const IgemmParams& P, hipStream_t st);
-constexpr int kNumIgemmWsVariants = 21;
+constexpr int kNumIgemmWsVariants = 24;
 extern const IgemmVariant kIgemmWsVariants[kNumIgemmWsVariants];
 hipError_t launch_igemm_ws(int variant, const IgemmParams& P, hipStream_t st);
 struct PatchVariant { int th, tw, bn, tps, stages; const char* fwd_name; const char* dgrad_name; };

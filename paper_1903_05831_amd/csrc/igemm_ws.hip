@@ -370,6 +370,9 @@ const IgemmVariant kIgemmWsVariants[kNumIgemmWsVariants] = {
     {64, 128, "igemm_fwd_ws_64x128x64_4w2f_s4", "igemm_dgrad_ws_64x128x64_4w2f_s4"},
     {64, 64, "igemm_fwd_ws_64x64x64_4w2f_s4_m16", "igemm_dgrad_ws_64x64x64_4w2f_s4_m16"},
     {64, 128, "igemm_fwd_ws_64x128x64_4w2f_s4_m16", "igemm_dgrad_ws_64x128x64_4w2f_s4_m16"},
+    {144, 128, "igemm_fwd_ws_144x128x64_6w2f_s3_m16", "igemm_dgrad_ws_144x128x64_6w2f_s3_m16"},
+    {144, 256, "igemm_fwd_ws_144x256x64_6w2f_s2_m16", "igemm_dgrad_ws_144x256x64_6w2f_s2_m16"},
+    {144, 64, "igemm_fwd_ws_144x64x64_3w2f_s4_m16", "igemm_dgrad_ws_144x64x64_3w2f_s4_m16"},
 };
 
 #define SDCONV_WS_CASE(idx, BM, BN, WGM, WGN, S, BK, NP)                                      \
@@ -414,6 +417,15 @@ hipError_t launch_igemm_ws(int variant, const IgemmParams& P, hipStream_t st)
         case 39: return launch_ws_variant<1, 64, 64, 2, 2, 4, 64, 2, 16>(P, st);
         case 40: return launch_ws_variant<0, 64, 128, 2, 2, 4, 64, 2, 16>(P, st);
         case 41: return launch_ws_variant<1, 64, 128, 2, 2, 4, 64, 2, 16>(P, st);
+        // 144-row tiles (three wave rows of 48): the 8400 / 33600 / 134400 pixel rows of the backbone
+        // stages make 59 / 234 / 934 of them, which fill 256 compute units to 91-92 % where 128-row
+        // tiles fill 52-69 %
+        case 42: return launch_ws_variant<0, 144, 128, 3, 2, 3, 64, 2, 16>(P, st);
+        case 43: return launch_ws_variant<1, 144, 128, 3, 2, 3, 64, 2, 16>(P, st);
+        case 44: return launch_ws_variant<0, 144, 256, 3, 2, 2, 64, 2, 16>(P, st);
+        case 45: return launch_ws_variant<1, 144, 256, 3, 2, 2, 64, 2, 16>(P, st);
+        case 46: return launch_ws_variant<0, 144, 64, 3, 1, 4, 64, 2, 16>(P, st);
+        case 47: return launch_ws_variant<1, 144, 64, 3, 1, 4, 64, 2, 16>(P, st);
         default: return hipErrorInvalidValue;
     }
 }

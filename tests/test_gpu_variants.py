@@ -76,7 +76,7 @@ WS_SHAPES = [
     (1, 31, 37, 136, 200, 3, 3, (1, 1), (1, 1), (1, 1)),    # short last channel slab, filter tail
     (1, 31, 37, 128, 264, 1, 1, (1, 1), (0, 0), (1, 1)),    # 1x1, more than one 256-wide column tile
 ]
-WS_VARIANTS = list(range(300, 321))
+WS_VARIANTS = list(range(300, 324))
 
 
 @pytest.mark.parametrize("variant", WS_VARIANTS)
