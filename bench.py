@@ -44,6 +44,10 @@ def main() -> int:
     ap.add_argument("--core-only", action="store_true",
                     help="only the timed step and its per-kernel pass (for profiler runs): skip the fused-epilogue, "
                          "second-workload and FP32 sections, whose launches would mix into the kernel statistics")
+    ap.add_argument("--layer", type=str, default="",
+                    help="run only this layer of the workload (with --passes), 20 times, and print its time: for "
+                         "per-kernel hardware-counter runs")
+    ap.add_argument("--passes", type=str, default="fwd", help="with --layer: comma-separated fwd,dgrad,wgrad")
     ap.add_argument("--detail", type=str, default="", help="write per-layer timings (JSON) to this file")
     ap.add_argument("--calib-copy-mib", type=int, default=0,
                     help="run one plain streaming kernel over this many MiB first (a known-size reference "
@@ -119,6 +123,27 @@ def main() -> int:
 
     def unscale():
         sd.grad_unscale_check(dw_flat, dw_total, inv_scale, flag, stream)
+
+    if args.layer:
+        sel = [c for c in calls if c[0].name == args.layer and c[1] in args.passes.split(",")]
+        if not sel:
+            print("bench.py: no such layer / pass", file=sys.stderr)
+            return 2
+        out = []
+        for c in sel:
+            for _ in range(3):
+                c[4](ws, stream)
+            torch.cuda.synchronize()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for _ in range(20):
+                c[4](ws, stream)
+            e1.record()
+            torch.cuda.synchronize()
+            ms = e0.elapsed_time(e1) / 20
+            out.append({"layer": c[0].name, "pass": c[1], "kernel": c[2], "us": ms * 1e3, "tflops": c[3] / ms / 1e9})
+        print(json.dumps({"single_layer": out}))
+        return 0
 
     # Schedule of one step on two streams, with the dependencies a training step has:
     #  - forward: the projection shortcut (".0p") of a stage's first block only needs the block
@@ -210,8 +235,14 @@ def main() -> int:
     per_call = []
     for i, c in enumerate(calls):
         ms = sum(ev[s][i][0].elapsed_time(ev[s][i][1]) for s in range(args.steps)) / args.steps
+        # the layer's own roofline: min(matrix peak, arithmetic intensity x HBM peak) on the bytes
+        # every tensor moves once
+        cbytes = c[0].compulsory_bytes(c[1])
+        roof = min(PEAK_F16_TFLOPS, c[3] / cbytes * PEAK_HBM_GBS / 1e3)
         per_call.append({"layer": c[0].name, "pass": c[1], "kernel": c[2], "us": ms * 1e3,
-                         "tflops": c[3] / ms / 1e9, "pct_peak": 100 * c[3] / ms / 1e9 / PEAK_F16_TFLOPS})
+                         "tflops": c[3] / ms / 1e9, "pct_peak": 100 * c[3] / ms / 1e9 / PEAK_F16_TFLOPS,
+                         "flop_per_byte": c[3] / cbytes, "roof_tflops": roof,
+                         "pct_of_roof": 100 * c[3] / ms / 1e9 / roof, "GBps": cbytes / ms / 1e6})
         gk = groups.setdefault(c[2], {"ms": 0.0, "flops": 0.0, "launches": 0, "pass": c[1], "bytes": 0.0})
         gk["ms"] += ms
         gk["flops"] += c[3]
@@ -243,18 +274,27 @@ def main() -> int:
 
     # ---- side figures ---------------------------------------------------------------------------
     # the nominal "~25M" gradient buffer of the workload description (24 * 2^20 elements)
+    # cold: six distinct buffers in rotation (604 MB, more than the 256 MB Infinity Cache holds);
+    # hot: one buffer over and over (it fits that cache, so the rate can exceed the HBM's)
     n_nom = 24 << 20
-    g_nom = torch.randn(n_nom, dtype=torch.float32, device=dev)
+    g_noms = [torch.randn(n_nom, dtype=torch.float32, device=dev) for _ in range(6)]
     e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    for _ in range(2):
-        sd.grad_unscale_check(g_nom, n_nom, inv_scale, flag, stream)
+    for b in g_noms:
+        sd.grad_unscale_check(b, n_nom, inv_scale, flag, stream)
     e0.record()
-    for _ in range(5):
-        sd.grad_unscale_check(g_nom, n_nom, inv_scale, flag, stream)
+    for _ in range(2):
+        for b in g_noms:
+            sd.grad_unscale_check(b, n_nom, inv_scale, flag, stream)
     e1.record()
     torch.cuda.synchronize()
-    nom_ms = e0.elapsed_time(e1) / 5
-    del g_nom
+    nom_ms = e0.elapsed_time(e1) / 12
+    e0.record()
+    for _ in range(6):
+        sd.grad_unscale_check(g_noms[0], n_nom, inv_scale, flag, stream)
+    e1.record()
+    torch.cuda.synchronize()
+    nom_hot_ms = e0.elapsed_time(e1) / 6
+    del g_noms
     # the optimizer tail that follows the check (not part of `value`): dynamic unscale, then the
     # SGD-momentum update with the fp16 weight cast and the loss-scale transition, on the
     # workload's 23 454 912 weights
@@ -426,7 +466,9 @@ def main() -> int:
         "roofline": roofline,
         "unscale": {"us": unscale_ms * 1e3, "GBps": unscale_gbs, "frac_hbm": unscale_gbs / PEAK_HBM_GBS,
                     "bytes": 8 * dw_total},
-        "unscale_nominal_25M": {"elements": n_nom, "us": nom_ms * 1e3, "GBps": 8.0 * n_nom / nom_ms / 1e6},
+        "unscale_nominal_25M": {"elements": n_nom, "us": nom_ms * 1e3, "GBps": 8.0 * n_nom / nom_ms / 1e6,
+                                "what": "cold: six buffers in rotation (604 MB); hot: one buffer repeated",
+                                "hot_us": nom_hot_ms * 1e3, "hot_GBps": 8.0 * n_nom / nom_hot_ms / 1e6},
         "optimizer_tail": {"what": "grad_unscale_check_dynamic + sgd_momentum_update on %d weights" % dw_total,
                            "us": tail_ms * 1e3, "bytes": 30 * dw_total,
                            "GBps": 30.0 * dw_total / tail_ms / 1e6,

@@ -8,8 +8,11 @@
 //
 // The four rows of a block are a row pitch apart, i.e. on the same banks for any pitch that is
 // a multiple of 256 bytes: 64-byte granules of a row are therefore XOR-swizzled with the row
-// number.  The LDS-DMA loads write LDS linearly, so the swizzle is applied on the global side,
-// by choosing which 16-byte chunk a lane fetches (swizzled_chunk).
+// number.  The 16x16x32 fragments read only 32 bytes of a row per instruction, from rows r..r+3
+// and r+8..r+11 in the same half of the wave, so the two 32-byte halves of a granule are swapped
+// in rows whose bit 3 is set (without it those reads are two-way bank conflicts: 20 % of the
+// weight-gradient kernel's cycles).  The LDS-DMA loads write LDS linearly, so the swizzle is
+// applied on the global side, by choosing which 16-byte chunk a lane fetches (swizzled_chunk).
 #pragma once
 #include <hip/hip_runtime.h>
 
@@ -36,14 +39,14 @@ __device__ __forceinline__ int sw_off(int row, int col)
     constexpr int pitch = BW * 2;
     int byte = col * 2;
     int gran = (byte >> 6) ^ (row & tr_gmask<BW>());
-    return row * pitch + (gran << 6) + (byte & 63);
+    return row * pitch + (gran << 6) + ((byte & 63) ^ (((row >> 3) & 1) << 5));
 }
 
 // Logical 16-byte chunk of row `row` that the lane filling physical chunk slot `pc` fetches.
 template <int BW>
 __device__ __forceinline__ int swizzled_chunk(int row, int pc)
 {
-    return (((pc >> 2) ^ (row & tr_gmask<BW>())) << 2) | (pc & 3);
+    return (((pc >> 2) ^ (row & tr_gmask<BW>())) << 2) | ((pc & 3) ^ (((row >> 3) & 1) << 1));
 }
 
 // Fragment of the 32 columns starting at col0 (a multiple of 32), contraction rows

@@ -50,8 +50,6 @@ __global__ __launch_bounds__(64 * WGM * WGN) void wgrad_dma_kernel(WgradParams P
     constexpr int PG = BP / RPG, PX = BP / RPX;         // DMA loads per thread and stage
     constexpr int GBYTES = BP * BM * 2, XBYTES = BP * BN * 2, STAGE = GBYTES + XBYTES;
     constexpr int INFLIGHT = (S - 2) * (PG + PX);
-    constexpr int GMG = (BM * 2 >= 256) ? 3 : (BM * 2 / 64 - 1);
-    constexpr int GMX = (BN * 2 >= 256) ? 3 : (BN * 2 / 64 - 1);
     static_assert((MF == 32 || MF == 16) && WM % MF == 0 && WN % MF == 0 && BP % KSTEP == 0, "wave tile");
     static_assert(PG >= 1 && PX >= 1 && BP % RPG == 0 && BP % RPX == 0 && RPG % 4 == 0 && RPX % 4 == 0, "staging");
     static_assert(S >= 2 && INFLIGHT < 64 && BP % 16 == 0 && BP <= 64 * NW, "pipeline");
@@ -95,14 +93,14 @@ __global__ __launch_bounds__(64 * WGM * WGN) void wgrad_dma_kernel(WgradParams P
 #pragma unroll
     for (int i = 0; i < PG; ++i) {
         int row = i * RPG + ft / CRG, pc = ft % CRG;
-        int lc = ((((pc >> 2) ^ (row & GMG)) << 2) | (pc & 3));
+        int lc = swizzled_chunk<BM>(row, pc);
         int k = k0 + lc * 8;
         g_off[i] = (k < P.K) ? (unsigned)((row * P.K + k) * 2) : kOutOfRange;
     }
 #pragma unroll
     for (int i = 0; i < PX; ++i) {
         int row = i * RPX + ft / CRX, pc = ft % CRX;
-        int lc = ((((pc >> 2) ^ (row & GMX)) << 2) | (pc & 3));
+        int lc = swizzled_chunk<BN>(row, pc);
         int c = c0 + lc * 8;
         x_row[i] = row;
         if (LINEAR) x_add[i] = (c < P.C) ? (unsigned)((row * P.C + c) * 2) : kOutOfRange;
