@@ -6,9 +6,11 @@ workload (N=2 images of 800x1344 plus 512 RoIs; 53 conv layers), in the order of
 step: conv2d_fwd for every layer first to last, then last to first conv2d_dgrad and
 conv2d_wgrad of each layer, then grad_unscale_check over all 23 454 912 fp32 weight-gradient
 elements.  The two gradients of a layer depend only on the incoming gradient, not on each
-other: with --streams 2 (default) the weight gradients (and the projection shortcuts) go to a
-second HIP stream (default priority, own workspace), each gated by an event so that it starts
-only when the gradient it consumes exists; --streams 1 keeps everything on one stream.  Inputs are synthetic (N(0,1) activations and gradients, He-normal weights), generated
+other, and the weight gradients of different layers do not depend on one another: with
+--streams 3 (default) the weight gradients are dealt in turn to two side HIP streams (default
+priority, a workspace each; the projection shortcuts go to the first of them), each gated by
+an event so that it starts only when the gradient it consumes exists; --streams 2 uses one
+side stream, --streams 1 keeps everything on one stream.  Inputs are synthetic (N(0,1) activations and gradients, He-normal weights), generated
 on the device before the timed region.
 
 Prints ONE JSON line.  `value` is algorithmic TFLOP/s of the whole step (2*N*Ho*Wo*K*R*S*C
@@ -39,8 +41,9 @@ def main() -> int:
     ap.add_argument("--steps", type=int, default=10)
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--streams", type=int, default=2, choices=(1, 2),
-                    help="2: weight gradients on a second stream, overlapping the data gradients")
+    ap.add_argument("--streams", type=int, default=3, choices=(1, 2, 3, 4),
+                    help="2: weight gradients on a second stream, overlapping the data gradients; "
+                         "3, 4: weight gradients dealt in turn to two or three side streams")
     ap.add_argument("--core-only", action="store_true",
                     help="only the timed step and its per-kernel pass (for profiler runs): skip the fused-epilogue, "
                          "second-workload and FP32 sections, whose launches would mix into the kernel statistics")
@@ -72,7 +75,8 @@ def main() -> int:
     torch.cuda.set_device(dev)
     main_stream = torch.cuda.current_stream()
     stream = main_stream.cuda_stream
-    side_stream = torch.cuda.Stream() if args.streams == 2 else None      # default priority
+    side_streams = [torch.cuda.Stream() for _ in range(args.streams - 1)]      # default priority
+    side_stream = side_streams[0] if side_streams else None
     stream2 = side_stream.cuda_stream if side_stream is not None else stream
     layers = workloads.CONFIGS[CONFIG_ID]
 
@@ -106,7 +110,8 @@ def main() -> int:
             ws_bytes = max(ws_bytes, sd.conv2d_workspace_bytes(d, pid))
         jobs.append((l, d, x, w, g, y, dx, dw))
     ws = torch.empty(ws_bytes, dtype=torch.uint8, device=dev)
-    ws2 = torch.empty(ws_bytes, dtype=torch.uint8, device=dev) if side_stream is not None else ws
+    side_ws = [torch.empty(ws_bytes, dtype=torch.uint8, device=dev) for _ in side_streams]   # one workspace per stream
+    ws2 = side_ws[0] if side_ws else ws
     inv_scale = 1.0 / LOSS_SCALE
 
     # (layer, pass name, kernel name, flops, closure(workspace, stream)) in training order:
@@ -145,14 +150,14 @@ def main() -> int:
         print(json.dumps({"single_layer": out}))
         return 0
 
-    # Schedule of one step on two streams, with the dependencies a training step has:
+    # Schedule of one step on the main and the side streams, with the dependencies a training step has:
     #  - forward: the projection shortcut (".0p") of a stage's first block only needs the block
     #    input, so it runs on the side stream next to the 0a-0b-0c branch; the next block waits
     #    for both;
     #  - backward: a layer's weight gradient needs the gradient of the layer's output, which the
     #    data gradient issued just before it on the main stream produces: an event recorded
-    #    there gates the side stream, so wgrad(l) runs beside dgrad(l) and never before its
-    #    input exists.  The shortcut's two gradients run on the side stream; the layer before
+    #    there gates the side stream that takes it (they take turns), so wgrad(l) runs beside
+    #    dgrad(l) and the weight gradients of its neighbours, and never before its input exists.  The shortcut's two gradients run on the side stream; the layer before
     #    the block waits for both branches.
     n_l = len(jobs)
     fwd_calls = calls[:n_l]
@@ -185,26 +190,32 @@ def main() -> int:
             c[4](ws, stream)
         e_dy = ev_pool[ei]; ei += 1
         e_dy.record(main_stream)                            # "the gradient the next layer consumes is ready"
+        turn = 0
         for i in range(0, len(bwd_calls), 2):
             cd, cw = bwd_calls[i], bwd_calls[i + 1]
             name = cd[0].name
-            side_stream.wait_event(e_dy)
             if name.endswith(".0p"):
+                side_stream.wait_event(e_dy)
                 cd[4](ws2, stream2)
                 cw[4](ws2, stream2)
                 pending_p = ev_pool[ei]; ei += 1
                 pending_p.record(side_stream)
                 continue
-            cw[4](ws2, stream2)
+            wst = side_streams[turn % len(side_streams)]    # weight gradients take the side streams in turn
+            wst.wait_event(e_dy)
+            cw[4](side_ws[turn % len(side_streams)], wst.cuda_stream)
+            turn += 1
             cd[4](ws, stream)
             if name.endswith(".0a") and pending_p is not None:
                 main_stream.wait_event(pending_p)           # block-input gradient = branch + shortcut
                 pending_p = None
             e_dy = ev_pool[ei]; ei += 1
             e_dy.record(main_stream)
-        main_stream.wait_stream(side_stream)                # all weight gradients done before the unscale
+        for st in side_streams:
+            main_stream.wait_stream(st)                     # all weight gradients done before the unscale
         unscale()
-        side_stream.wait_stream(main_stream)                # the next step follows this unscale
+        for st in side_streams:
+            st.wait_stream(main_stream)                     # the next step follows this unscale
 
     flops_per_step = 3 * sum(l.flops for l in layers)
 
