@@ -108,21 +108,37 @@ __global__ __launch_bounds__(64 * WGM * WGN) void wgrad_dma_kernel(WgradParams P
     }
     const int4v rsrcX = make_rsrc(P.X, (unsigned)(P.N * P.H * P.W * P.C) * 2u);
 
-    // x offset table of one step: lane t < BP decodes pixel p0 + t
-    auto fill_table = [&](int step, int slot) {
+    // x offset table of one step: lane t < BP holds pixel p0 + t.  The steps come in order, so
+    // the lane keeps its pixel's (image, row, column) and moves it on by BP pixels per step with
+    // two carries instead of dividing again (the divisions cost 5 % of a 3x3 layer's kernel).
+    int tb_p = 0, tb_n = 0, tb_ho = 0, tb_wo = 0;
+    const int hw = P.Ho * P.Wo;
+    const int adv_n = BP / hw, adv_ho = (BP % hw) / P.Wo, adv_wo = (BP % hw) % P.Wo;
+    if (!LINEAR && tid < BP) {
+        tb_p = step0 * BP + tid;
+        tb_n = tb_p / hw;
+        const int rem = tb_p - tb_n * hw;
+        tb_ho = rem / P.Wo;
+        tb_wo = rem - tb_ho * P.Wo;
+    }
+    auto fill_table = [&](int slot) {
         if (LINEAR) return;
         if (tid < BP) {
-            int p = (step0 + step) * BP + tid;
             unsigned off = kOutOfRange;
-            if (p < P.P) {
-                int n = p / (P.Ho * P.Wo);
-                int rem = p - n * (P.Ho * P.Wo);
-                int ho = rem / P.Wo, wo = rem - ho * P.Wo;
-                int h = ho * P.sh + oh, w = wo * P.sw + ow;
+            if (tb_p < P.P) {
+                int h = tb_ho * P.sh + oh, w = tb_wo * P.sw + ow;
                 if ((unsigned)h < (unsigned)P.H && (unsigned)w < (unsigned)P.W)
-                    off = (unsigned)((((n * P.H + h) * P.W + w) * P.C) * 2);
+                    off = (unsigned)((((tb_n * P.H + h) * P.W + w) * P.C) * 2);
             }
             xtab[slot * BP + tid] = off;
+            tb_p += BP;
+            tb_wo += adv_wo;
+            int carry = tb_wo >= P.Wo;
+            tb_wo -= carry ? P.Wo : 0;
+            tb_ho += adv_ho + carry;
+            carry = tb_ho >= P.Ho;
+            tb_ho -= carry ? P.Ho : 0;
+            tb_n += adv_n + carry;
         }
     };
 
@@ -188,7 +204,7 @@ __global__ __launch_bounds__(64 * WGM * WGN) void wgrad_dma_kernel(WgradParams P
     if (nsteps > 0) {
 #pragma unroll
         for (int q = 0; q < S; ++q)
-            if (q < nsteps) fill_table(q, q);
+            if (q < nsteps) fill_table(q);
         if (!LINEAR) __syncthreads();
         int issued = 0;
 #pragma unroll
@@ -206,7 +222,7 @@ __global__ __launch_bounds__(64 * WGM * WGN) void wgrad_dma_kernel(WgradParams P
             }
             // table of step it+S (read by the issue of the next iteration) reuses the slot of
             // step `it`, whose loads were issued S-1 iterations ago
-            if (it + S < nsteps) fill_table(it + S, cs);
+            if (it + S < nsteps) fill_table(cs);
             compute(cs);
             cs = (cs + 1 == S) ? 0 : cs + 1;
         }
