@@ -87,6 +87,9 @@ def main() -> int:
     ap.add_argument("--layers", type=str, default="",
                     help="comma-separated name fragments: tune only matching layers (a partial table, for experiments)")
     ap.add_argument("--fwd-dgrad-only", action="store_true", help="skip the weight-gradient search")
+    ap.add_argument("--wgrad-only", action="store_true",
+                    help="search the weight gradient only; the data gradient beside it runs the variant of the "
+                         "table built into the library (use with --keep)")
     ap.add_argument("--out", type=str, default=os.path.join(HERE, "csrc", "tuned_table.inc"))
     ap.add_argument("--wgrad-solo", action="store_true",
                     help="pick the weight-gradient variant by its time alone instead of beside the data gradient")
@@ -99,7 +102,8 @@ def main() -> int:
     st = torch.cuda.current_stream().cuda_stream
     side = torch.cuda.Stream()
     st2 = side.cuda_stream
-    os.environ["SDCONV_NO_TUNED_TABLE"] = "1"
+    if not args.wgrad_only:
+        os.environ["SDCONV_NO_TUNED_TABLE"] = "1"
     seen = set()
     lines = []
     for cfg in [int(c) for c in args.configs.split(",")]:
@@ -125,7 +129,8 @@ def main() -> int:
             dx = torch.empty(l.x_shape, device=dev, dtype=torch.float16)
             dw = torch.empty(l.w_shape, device=dev, dtype=torch.float32)
             geom = f"{l.N},{l.H},{l.W},{l.C},{l.K},{l.R},{l.S},{l.stride},{l.stride},{l.pad},{l.pad},{l.dil},{l.dil}"
-            for pid, pname in ((sd.FWD, "fwd"), (sd.DGRAD, "dgrad")):
+            best_dgrad = None
+            for pid, pname in (() if args.wgrad_only else ((sd.FWD, "fwd"), (sd.DGRAD, "dgrad"))):
                 results = []
                 for v in FWD_DGRAD_VARIANTS:
                     os.environ["SDCONV_IGEMM_VARIANT"] = str(v)
@@ -150,7 +155,8 @@ def main() -> int:
             # training step: what counts is how long the pair takes, which favours variants that
             # leave compute units and bandwidth to the other kernel.
             results = []
-            os.environ["SDCONV_IGEMM_VARIANT"] = str(best_dgrad)
+            if best_dgrad is not None:
+                os.environ["SDCONV_IGEMM_VARIANT"] = str(best_dgrad)
             ws_d = torch.empty(max(sd.conv2d_workspace_bytes(d, sd.DGRAD), 256), dtype=torch.uint8, device=dev)
             fn_d = lambda i: sd.conv2d_dgrad(d, gs[i], wts[i], dx, ws_d, st)
             for wv in WGRAD_VARIANTS:
@@ -171,9 +177,9 @@ def main() -> int:
                         best_t, worse = t, 0
                     else:
                         worse += 1
-                        if worse >= 3:
+                        if worse >= 4:
                             break
-            os.environ.pop("SDCONV_IGEMM_VARIANT")
+            os.environ.pop("SDCONV_IGEMM_VARIANT", None)
             os.environ.pop("SDCONV_WGRAD_SPLITS", None)
             os.environ.pop("SDCONV_WGRAD_VARIANT", None)
             t, wv, sp = min(results)
