@@ -11,7 +11,8 @@
 //             one filter row (transposing LDS read of the patch: 4 consecutive output pixels
 //             of one padded input pixel), contraction = output pixels along the tile row.
 // Both are bound by the HBM traffic of the K-channel tensor (y or dy), so the y tile is
-// written, and the dy tile read, as whole 128-byte lines.
+// written, and the dy tile read, as whole 128-byte lines.  A workgroup walks over several
+// tiles and fetches the next tile's inputs into registers while it multiplies the current one.
 #include "common.h"
 #include "thin.h"
 
@@ -55,26 +56,65 @@ __global__ __launch_bounds__(256) void thin_pack_filter_kernel(const __half* __r
     wp[i] = v;
 }
 
-// Copies the padded input patch of one output tile into LDS ([PH][PW] pixels of 8 bytes).
-__device__ __forceinline__ void load_patch(const ThinParams& P, unsigned char* patch, int n, int ho0, int wo0,
-                                           int tid)
+// The padded input patch of one output tile goes to LDS ([PH][PW] pixels of 8 bytes) in two
+// halves: patch_fetch sends the loads of up to kPU pixels per thread, all of them in flight at
+// once (unconditional loads from clamped addresses: a load under a branch would be waited for
+// before the next one is sent), and patch_put writes them to LDS.  Between the two the caller
+// multiplies the previous tile, so the latency of the loads is hidden.
+constexpr int kPU = 6;                  // 256 threads x 6 pixels cover the 21 x 70 patch of a 7x7 stride-2 stem
+typedef uint2v PatchRegs[kPU];      // (channels 0-1, channels 2-3) of the pixels a thread carries
+
+__device__ __forceinline__ void patch_fetch(const ThinParams& P, int n, int ho0, int wo0, int tid, int first,
+                                            PatchRegs& r)
 {
     const unsigned short* X = reinterpret_cast<const unsigned short*>(P.X);
     const int h0 = ho0 * P.sh - P.ph, w0 = wo0 * P.sw - P.pw;
-    for (int idx = tid; idx < P.PH * P.PW; idx += 256) {
-        int prow = idx / P.PW, pcol = idx - prow * P.PW;
-        int h = h0 + prow, w = w0 + pcol;
-        unsigned lo = 0, hi = 0;
-        if ((unsigned)h < (unsigned)P.H && (unsigned)w < (unsigned)P.W) {
-            const unsigned short* px = X + (((long)n * P.H + h) * P.W + w) * P.C;
-            lo = px[0];
-            if (P.C > 1) lo |= (unsigned)px[1] << 16;
-            if (P.C > 2) hi = px[2];
-            if (P.C > 3) hi |= (unsigned)px[3] << 16;
-        }
-        uint2v v = {lo, hi};
-        *reinterpret_cast<uint2v*>(patch + idx * 8) = v;
+    const int total = P.PH * P.PW;
+    const int c1 = P.C > 1 ? 1 : 0, c2 = P.C > 2 ? 2 : 0, c3 = P.C > 3 ? 3 : 0;
+#pragma unroll
+    for (int u = 0; u < kPU; ++u) {
+        const int idx = first + tid + 256 * u;
+        const int prow = idx / P.PW, pcol = idx - prow * P.PW;
+        const int h = h0 + prow, w = w0 + pcol;
+        const bool ok = idx < total && (unsigned)h < (unsigned)P.H && (unsigned)w < (unsigned)P.W;
+        const unsigned short* px = X + (ok ? (((long)n * P.H + h) * P.W + w) * P.C : 0);
+        const unsigned v0 = px[0], v1 = px[c1], v2 = px[c2], v3 = px[c3];
+        unsigned lo = v0 | (c1 ? v1 << 16 : 0u);
+        unsigned hi = (c2 ? v2 : 0u) | (c3 ? v3 << 16 : 0u);
+        r[u].x = ok ? lo : 0u;
+        r[u].y = ok ? hi : 0u;
     }
+}
+
+__device__ __forceinline__ void patch_put(const ThinParams& P, unsigned char* patch, int tid, int first,
+                                          const PatchRegs& r)
+{
+    const int total = P.PH * P.PW;
+#pragma unroll
+    for (int u = 0; u < kPU; ++u) {
+        const int idx = first + tid + 256 * u;
+        if (idx < total) *reinterpret_cast<uint2v*>(patch + idx * 8) = r[u];
+    }
+}
+
+// Pixels of the patch beyond the first 256 * kPU (filters or strides larger than a stem's).
+__device__ __forceinline__ void patch_rest(const ThinParams& P, unsigned char* patch, int n, int ho0, int wo0, int tid)
+{
+    for (int first = 256 * kPU; first < P.PH * P.PW; first += 256 * kPU) {
+        PatchRegs t;
+        patch_fetch(P, n, ho0, wo0, tid, first, t);
+        patch_put(P, patch, tid, first, t);
+    }
+}
+
+__device__ __forceinline__ void tile_origin(const ThinParams& P, int tile, int& n, int& ho0, int& wo0)
+{
+    const int tw = tile % P.tiles_w;
+    tile /= P.tiles_w;
+    const int th = tile % P.tiles_h;
+    n = tile / P.tiles_h;
+    ho0 = th * kTH;
+    wo0 = tw * kTW;
 }
 
 __global__ __launch_bounds__(256) void thin_fwd_kernel(ThinParams P)
@@ -93,16 +133,25 @@ __global__ __launch_bounds__(256) void thin_fwd_kernel(ThinParams P)
         for (int i = tid; i < P.R * 4 * kKT; i += 256) reinterpret_cast<uint4v*>(ldsW)[i] = src[i];
     }
 
+    PatchRegs pr;
+    if ((int)blockIdx.x < P.ntiles) {
+        int n, ho0, wo0;
+        tile_origin(P, blockIdx.x, n, ho0, wo0);
+        patch_fetch(P, n, ho0, wo0, tid, 0, pr);
+    }
     for (int tile = blockIdx.x; tile < P.ntiles; tile += gridDim.x) {
-        int t = tile;
-        const int tw = t % P.tiles_w; t /= P.tiles_w;
-        const int th = t % P.tiles_h;
-        const int n = t / P.tiles_h;
-        const int ho0 = th * kTH, wo0 = tw * kTW;
+        int n, ho0, wo0;
+        tile_origin(P, tile, n, ho0, wo0);
 
         __syncthreads();                       // previous tile fully consumed
-        load_patch(P, patch, n, ho0, wo0, tid);
+        patch_put(P, patch, tid, 0, pr);
+        patch_rest(P, patch, n, ho0, wo0, tid);
         __syncthreads();
+        if (tile + (int)gridDim.x < P.ntiles) {    // the next tile's patch travels while this one is multiplied
+            int n2, ho2, wo2;
+            tile_origin(P, tile + gridDim.x, n2, ho2, wo2);
+            patch_fetch(P, n2, ho2, wo2, tid, 0, pr);
+        }
 
         float16v acc[2][2];
 #pragma unroll
@@ -205,29 +254,53 @@ __global__ __launch_bounds__(256) void thin_wgrad_kernel(ThinParams P)
 #pragma unroll
             for (int e = 0; e < 16; ++e) acc[a][b][e] = 0.f;
 
-    for (int tile = blockIdx.x; tile < P.ntiles; tile += gridDim.x) {
-        int t = tile;
-        const int tw = t % P.tiles_w; t /= P.tiles_w;
-        const int th = t % P.tiles_h;
-        const int n = t / P.tiles_h;
-        const int ho0 = th * kTH, wo0 = tw * kTW;
-
-        __syncthreads();
-        load_patch(P, patch, n, ho0, wo0, tid);
-        // dy tile: 256 pixels x 128 bytes, 8 lanes per pixel, 64-byte granules swizzled by pixel parity
+    // dy tile: 256 pixels x 128 bytes, 8 lanes per pixel; like the patch it is fetched into
+    // registers one tile ahead and written to LDS when the previous tile has been multiplied
+    auto dy_fetch = [&](int n, int ho0, int wo0, uint4v (&gv)[8]) {
 #pragma unroll
         for (int i = 0; i < 8; ++i) {
-            int c = tid + 256 * i;
-            int pix = c >> 3, part = c & 7;
-            int ho = ho0 + pix / kTW, wo = wo0 + pix % kTW;
-            int k = kt * kKT + part * 8;
-            uint4v v = {0u, 0u, 0u, 0u};
-            if (ho < P.Ho && wo < P.Wo && k < P.K)
-                v = *reinterpret_cast<const uint4v*>(P.G + ((((long)n * P.Ho + ho) * P.Wo + wo) * P.K + k));
-            int gran = (part >> 2) ^ (pix & 1);
-            *reinterpret_cast<uint4v*>(gt + pix * 128 + gran * 64 + (part & 3) * 16) = v;
+            const int c = tid + 256 * i;
+            const int pix = c >> 3, part = c & 7;
+            const int ho = ho0 + pix / kTW, wo = wo0 + pix % kTW;
+            const int k = kt * kKT + part * 8;
+            const bool ok = ho < P.Ho && wo < P.Wo && k < P.K;
+            const uint4v* src = reinterpret_cast<const uint4v*>(
+                P.G + (ok ? (((long)n * P.Ho + ho) * P.Wo + wo) * P.K + k : 0));
+            const uint4v v = *src;
+            const uint4v z = {0u, 0u, 0u, 0u};
+            gv[i] = ok ? v : z;
+        }
+    };
+    PatchRegs pr;
+    uint4v gv[8];
+    if ((int)blockIdx.x < P.ntiles) {
+        int n, ho0, wo0;
+        tile_origin(P, blockIdx.x, n, ho0, wo0);
+        patch_fetch(P, n, ho0, wo0, tid, 0, pr);
+        dy_fetch(n, ho0, wo0, gv);
+    }
+    for (int tile = blockIdx.x; tile < P.ntiles; tile += gridDim.x) {
+        int n, ho0, wo0;
+        tile_origin(P, tile, n, ho0, wo0);
+
+        __syncthreads();
+        patch_put(P, patch, tid, 0, pr);
+        patch_rest(P, patch, n, ho0, wo0, tid);
+        // 64-byte granules of a dy row swizzled by pixel parity
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            const int c = tid + 256 * i;
+            const int pix = c >> 3, part = c & 7;
+            const int gran = (part >> 2) ^ (pix & 1);
+            *reinterpret_cast<uint4v*>(gt + pix * 128 + gran * 64 + (part & 3) * 16) = gv[i];
         }
         __syncthreads();
+        if (tile + (int)gridDim.x < P.ntiles) {
+            int n2, ho2, wo2;
+            tile_origin(P, tile + gridDim.x, n2, ho2, wo2);
+            patch_fetch(P, n2, ho2, wo2, tid, 0, pr);
+            dy_fetch(n2, ho2, wo2, gv);
+        }
 
         for (int row = 0; row < kTH; ++row) {
 #pragma unroll
@@ -289,9 +362,20 @@ __global__ __launch_bounds__(256) void thin_wgrad_reduce_kernel(const float* __r
     const int k = blockIdx.x / R, r = blockIdx.x % R;
     const int kt = k / kKT, kk = k % kKT;
     const int slot = threadIdx.x & 31, part = threadIdx.x >> 5;
-    float s = 0.f;
-    for (int wg = part; wg < nwg; wg += 8)
-        s += partial[((((long)wg * ktiles + kt) * kKT + kk) * R + r) * 32 + slot];
+    // four independent chains so that four loads are in flight per thread; the order of the
+    // additions depends on nwg only
+    const long pitch = (long)ktiles * kKT * R * 32;
+    const float* src = partial + (((long)kt * kKT + kk) * R + r) * 32 + slot;
+    float s0 = 0.f, s1 = 0.f, s2 = 0.f, s3 = 0.f;
+    int wg = part;
+    for (; wg + 24 < nwg; wg += 32) {
+        s0 += src[(long)wg * pitch];
+        s1 += src[(long)(wg + 8) * pitch];
+        s2 += src[(long)(wg + 16) * pitch];
+        s3 += src[(long)(wg + 24) * pitch];
+    }
+    for (; wg < nwg; wg += 8) s0 += src[(long)wg * pitch];
+    const float s = (s0 + s1) + (s2 + s3);
     red[part][slot] = s;
     __syncthreads();
     if (part == 0) {
@@ -417,10 +501,19 @@ size_t thin_packed_filter_bytes(const Geom& g)
     return (size_t)ktiles * g.R * 4 * kKT * 16;
 }
 
+// Workgroups walk over the tiles with a stride of the grid size: the grid is the smallest one
+// that gives every workgroup the same number of tiles (2100 tiles on 512 resident workgroups:
+// 420 workgroups of 5 tiles, not 512 of which a tenth take a fifth tile while the rest wait).
+static int balanced_grid(int ntiles, int resident)
+{
+    const int per_wg = (ntiles + resident - 1) / resident;
+    return (ntiles + per_wg - 1) / per_wg;
+}
+
 int thin_wgrad_workgroups(const Geom& g)
 {
     int ntiles = g.N * ((g.Ho + kTH - 1) / kTH) * ((g.Wo + kTW - 1) / kTW);
-    return ntiles < 512 ? ntiles : 512;
+    return balanced_grid(ntiles, 512);
 }
 
 size_t thin_wgrad_partial_bytes(const Geom& g)
@@ -472,7 +565,7 @@ hipError_t launch_thin_fwd(const Geom& g, const __half* x, const __half* w, __ha
         if (e != hipSuccess) return e;
         configured = true;
     }
-    int grid = P.ntiles < 1024 ? P.ntiles : 1024;
+    const int grid = balanced_grid(P.ntiles, 512);     // two workgroups per compute unit fit in LDS
     hipLaunchKernelGGL(thin_fwd_kernel, dim3(grid, ktiles), dim3(256), lds, st, P);
     return hipGetLastError();
 }
