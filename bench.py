@@ -35,6 +35,19 @@ CONFIG_ID = 5
 LOSS_SCALE = 1024.0
 
 
+def device_clock_mhz() -> float:
+    """Peak engine clock the HIP runtime reports for device 0 (hipDeviceAttributeClockRate, kHz)."""
+    import ctypes
+    try:
+        hip = ctypes.CDLL("libamdhip64.so")
+        v = ctypes.c_int(0)
+        if hip.hipDeviceGetAttribute(ctypes.byref(v), 5, 0) != 0:      # 5 = hipDeviceAttributeClockRate
+            return 0.0
+        return v.value / 1e3
+    except OSError:
+        return 0.0
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -502,7 +515,9 @@ def main() -> int:
             "fp32_tflops": f32_flops / f32_ms / 1e9, "fp32_frac_of_peak": f32_flops / f32_ms / 1e9 / 157.3,
             "fp16_tflops": f32_flops / f16_ms / 1e9,
             "paper": "Fig. 1(b): 2.0x end to end (whole training step, hardware not stated)"},
-        "device": {"name": props.name, "compute_units": cus, "mfma_only_tflops": ceiling_tflops, "mfma_only_frac_of_peak": ceiling_tflops / PEAK_F16_TFLOPS},
+        "device": {"name": props.name, "arch": getattr(props, "gcnArchName", ""), "compute_units": cus,
+                   "clock_mhz": device_clock_mhz(), "rocm": torch.version.hip,
+                   "mfma_only_tflops": ceiling_tflops, "mfma_only_frac_of_peak": ceiling_tflops / PEAK_F16_TFLOPS},
         "ms_per_step_with_events": instrumented_ms,
         "one_stream_events": {"tflops": flops_per_step / instrumented_ms / 1e9,
                               "tflops_without_stem_dgrad": (flops_per_step - stem_flops)
