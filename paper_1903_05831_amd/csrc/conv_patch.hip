@@ -40,7 +40,10 @@ typedef float float4p __attribute__((ext_vector_type(4)));
 // TPS: taps per pipeline step (must divide R*S).  A step of one tap is only 64 deep; on small
 // tiles the barrier and the wait then cost as much as the MFMAs between them, so a step can
 // cover a whole filter row (TPS = 3): the ring stage holds TPS filter slabs.
-template <int MODE, int TH, int TW, int BN, int WGM, int WGN, int SB, int MF = 32, int NIW = 0, int TPS = 1, bool TAIL = false>
+// NPB: patch buffers.  Two alternate between channel slabs; a layer with 64 source channels has
+// one slab and needs one buffer, which lets two or three workgroups share a compute unit's LDS
+// (its 134 400-pixel maps make 546-1050 blocks: at one workgroup per unit they run in 3-4 rounds).
+template <int MODE, int TH, int TW, int BN, int WGM, int WGN, int SB, int MF = 32, int NIW = 0, int TPS = 1, int NPB = 2, bool TAIL = false>
 __global__ __launch_bounds__(64 * WGM * WGN) void conv_patch_kernel(IgemmParams P)
 {
     constexpr int EH = 2, EW = 2;                   // extra patch rows / columns
@@ -60,10 +63,11 @@ __global__ __launch_bounds__(64 * WGM * WGN) void conv_patch_kernel(IgemmParams 
     constexpr int D = SB - 1;                              // filter stages in flight
     static_assert((MF == 32 || MF == 16) && NI >= 1 && NI < NW && WM % MF == 0 && WN % MF == 0 && BN % (8 * NI) == 0, "tile shape");
     static_assert(SB >= 2 && NPL + D * PB < 64, "loads in flight");   // vmcnt is a 6-bit counter
+    static_assert(NPB == 1 || NPB == 2, "patch buffers");
 
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
     const unsigned lds0 = (unsigned)(size_t)(__attribute__((address_space(3))) unsigned char*)smem;
-    unsigned char* bring = smem + 2 * PATCHB;
+    unsigned char* bring = smem + NPB * PATCHB;
     int* tap_bo = reinterpret_cast<int*>(bring + SB * BSTAGE);   // byte offset of the tap in a filter row
     int* tap_po = tap_bo + kMaxTaps;                              // patch-pixel displacement of the tap
 
@@ -135,7 +139,7 @@ __global__ __launch_bounds__(64 * WGM * WGN) void conv_patch_kernel(IgemmParams 
 
     auto issue_patch = [&](int kc) {                // slab kc into buffer kc & 1
         const unsigned soff = (unsigned)__builtin_amdgcn_readfirstlane(kc * 128);
-        const unsigned base = (unsigned)__builtin_amdgcn_readfirstlane((int)(lds0 + (kc & 1) * PATCHB + fw * 1024));
+        const unsigned base = (unsigned)__builtin_amdgcn_readfirstlane((int)(lds0 + (kc & (NPB - 1)) * PATCHB + fw * 1024));
 #pragma unroll
         for (int q = 0; q < NPL; ++q) dma16(a_off[q], rsrcA, soff, base + q * NI * 1024);
     };
@@ -146,7 +150,7 @@ __global__ __launch_bounds__(64 * WGM * WGN) void conv_patch_kernel(IgemmParams 
             const unsigned soff = (unsigned)__builtin_amdgcn_readfirstlane(
                 tap_bo[nx_grp * TPS + tt] + (MODE == 0 ? nx_kc * 128 : nx_kc * 64 * P.b_row_pitch * 2));
             const unsigned base = (unsigned)__builtin_amdgcn_readfirstlane(
-                (int)(lds0 + 2 * PATCHB + nx_stage * BSTAGE + tt * BSLAB + fw * 1024));
+                (int)(lds0 + NPB * PATCHB + nx_stage * BSTAGE + tt * BSLAB + fw * 1024));
 #pragma unroll
             for (int p = 0; p < PB1; ++p) dma16(b_off[p], rsrcB, soff, base + p * NI * 1024);
         }
@@ -176,7 +180,7 @@ __global__ __launch_bounds__(64 * WGM * WGN) void conv_patch_kernel(IgemmParams 
             for (int e = 0; e < ACCN; ++e) acc[a][b][e] = 0.f;
 
     auto compute = [&](int kc, int grp, int stage) {
-        const unsigned char* pa = smem + (kc & 1) * PATCHB;
+        const unsigned char* pa = smem + (kc & (NPB - 1)) * PATCHB;
 #pragma unroll
         for (int tt = 0; tt < TPS; ++tt) {
             const unsigned char* sb = bring + stage * BSTAGE + tt * BSLAB;
@@ -245,7 +249,7 @@ __global__ __launch_bounds__(64 * WGM * WGN) void conv_patch_kernel(IgemmParams 
     }
 
     // ---- epilogue ------------------------------------------------------------------------------
-    static_assert(NW * epilogue_strip_bytes<WN, MF>() <= 2 * PATCHB + SB * TPS * BN * 128,
+    static_assert(NW * epilogue_strip_bytes<WN, MF>() <= NPB * PATCHB + SB * TPS * BN * 128,
                   "epilogue strips fit in the patch buffers and the filter ring");
     __builtin_amdgcn_s_barrier();                   // everybody is done reading the last patch and filter stage
     store_rows_via_lds<FM, FN, MF, TAIL>(acc, smem + wave * epilogue_strip_bytes<WN, MF>(), lane, n0 + wn * WN, P,
@@ -257,33 +261,34 @@ __global__ __launch_bounds__(64 * WGM * WGN) void conv_patch_kernel(IgemmParams 
     });
 }
 
-template <int MODE, int TH, int TW, int BN, int WGM, int WGN, int SB, int MF = 32, int NIW = 0, int TPS = 1, bool TAIL>
+template <int MODE, int TH, int TW, int BN, int WGM, int WGN, int SB, int MF = 32, int NIW = 0, int TPS = 1, int NPB = 2, bool TAIL>
 static hipError_t launch_patch_variant_impl(const IgemmParams& P, hipStream_t st)
 {
     if ((P.R * P.S) % TPS != 0 || (P.R * P.S) / TPS < SB - 1) return hipErrorInvalidValue;
+    if (NPB == 1 && P.Cs != 64) return hipErrorInvalidValue;      // one patch buffer = one channel slab
     constexpr int NI = NIW ? NIW : WGM * WGN / 2;
     constexpr int NPL = ((TH + 2) * (TW + 2) + 8 * NI - 1) / (8 * NI);
-    constexpr size_t lds = (size_t)2 * NPL * NI * 1024 + (size_t)SB * TPS * BN * 128 + 2 * kMaxTaps * sizeof(int);
+    constexpr size_t lds = (size_t)NPB * NPL * NI * 1024 + (size_t)SB * TPS * BN * 128 + 2 * kMaxTaps * sizeof(int);
     static_assert(lds <= 160 * 1024, "LDS budget");
     static bool configured = false;
     if (!configured) {
         hipError_t e = hipFuncSetAttribute(
-            reinterpret_cast<const void*>(&conv_patch_kernel<MODE, TH, TW, BN, WGM, WGN, SB, MF, NIW, TPS, TAIL>),
+            reinterpret_cast<const void*>(&conv_patch_kernel<MODE, TH, TW, BN, WGM, WGN, SB, MF, NIW, TPS, NPB, TAIL>),
             hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         if (e != hipSuccess) return e;
         configured = true;
     }
     const int grid = ((P.total_tiles + 63) / 64) * 64;
-    hipLaunchKernelGGL((conv_patch_kernel<MODE, TH, TW, BN, WGM, WGN, SB, MF, NIW, TPS, TAIL>), dim3(grid), dim3(64 * WGM * WGN),
+    hipLaunchKernelGGL((conv_patch_kernel<MODE, TH, TW, BN, WGM, WGN, SB, MF, NIW, TPS, NPB, TAIL>), dim3(grid), dim3(64 * WGM * WGN),
                        lds, st, P);
     return hipGetLastError();
 }
 
-template <int MODE, int TH, int TW, int BN, int WGM, int WGN, int SB, int MF = 32, int NIW = 0, int TPS = 1>
+template <int MODE, int TH, int TW, int BN, int WGM, int WGN, int SB, int MF = 32, int NIW = 0, int TPS = 1, int NPB = 2>
 static hipError_t launch_patch_variant(const IgemmParams& P, hipStream_t st)
 {
     // the tail has kernels of its own: see store_rows_via_lds
-    return P.ep.any() ? launch_patch_variant_impl<MODE, TH, TW, BN, WGM, WGN, SB, MF, NIW, TPS, true>(P, st) : launch_patch_variant_impl<MODE, TH, TW, BN, WGM, WGN, SB, MF, NIW, TPS, false>(P, st);
+    return P.ep.any() ? launch_patch_variant_impl<MODE, TH, TW, BN, WGM, WGN, SB, MF, NIW, TPS, NPB, true>(P, st) : launch_patch_variant_impl<MODE, TH, TW, BN, WGM, WGN, SB, MF, NIW, TPS, NPB, false>(P, st);
 }
 
 const PatchVariant kPatchVariants[kNumPatchVariants] = {
@@ -309,6 +314,13 @@ const PatchVariant kPatchVariants[kNumPatchVariants] = {
     {10, 14, 64, 3, 4, "conv_fwd_patch_10x14x64_6w_s4_m16_t3", "conv_dgrad_patch_10x14x64_6w_s4_m16_t3"},
     {16, 16, 64, 3, 3, "conv_fwd_patch_16x16x64_s3_m16_t3_2f", "conv_dgrad_patch_16x16x64_s3_m16_t3_2f"},
     {8, 16, 128, 3, 2, "conv_fwd_patch_8x16x128_s2_m16_t3", "conv_dgrad_patch_8x16x128_s2_m16_t3"},
+    // one patch buffer: layers with 64 source channels only
+    {16, 16, 64, 1, 3, "conv_fwd_patch_16x16x64_s3_m16_1p", "conv_dgrad_patch_16x16x64_s3_m16_1p", 1},
+    {16, 16, 64, 3, 2, "conv_fwd_patch_16x16x64_s2_m16_t3_1p", "conv_dgrad_patch_16x16x64_s2_m16_t3_1p", 1},
+    {10, 14, 64, 1, 3, "conv_fwd_patch_10x14x64_6w_s3_m16_1p", "conv_dgrad_patch_10x14x64_6w_s3_m16_1p", 1},
+    {10, 14, 64, 3, 2, "conv_fwd_patch_10x14x64_6w_s2_m16_t3_1p", "conv_dgrad_patch_10x14x64_6w_s2_m16_t3_1p", 1},
+    {8, 16, 64, 1, 3, "conv_fwd_patch_8x16x64_s3_m16_1p", "conv_dgrad_patch_8x16x64_s3_m16_1p", 1},
+    {8, 16, 64, 3, 2, "conv_fwd_patch_8x16x64_s2_m16_t3_1p", "conv_dgrad_patch_8x16x64_s2_m16_t3_1p", 1},
 };
 
 #define SDCONV_PATCH_CASE(idx, TH, TW, BN, WGM, WGN, SB)                                      \
@@ -357,6 +369,18 @@ hipError_t launch_conv_patch(int variant, const IgemmParams& P, hipStream_t st)
         case 41: return launch_patch_variant<1, 16, 16, 64, 4, 2, 3, 16, 2, 3>(P, st);
         case 42: return launch_patch_variant<0, 8, 16, 128, 2, 4, 2, 16, 0, 3>(P, st);
         case 43: return launch_patch_variant<1, 8, 16, 128, 2, 4, 2, 16, 0, 3>(P, st);
+        case 44: return launch_patch_variant<0, 16, 16, 64, 4, 2, 3, 16, 0, 1, 1>(P, st);
+        case 45: return launch_patch_variant<1, 16, 16, 64, 4, 2, 3, 16, 0, 1, 1>(P, st);
+        case 46: return launch_patch_variant<0, 16, 16, 64, 4, 2, 2, 16, 0, 3, 1>(P, st);
+        case 47: return launch_patch_variant<1, 16, 16, 64, 4, 2, 2, 16, 0, 3, 1>(P, st);
+        case 48: return launch_patch_variant<0, 10, 14, 64, 3, 2, 3, 16, 2, 1, 1>(P, st);
+        case 49: return launch_patch_variant<1, 10, 14, 64, 3, 2, 3, 16, 2, 1, 1>(P, st);
+        case 50: return launch_patch_variant<0, 10, 14, 64, 3, 2, 2, 16, 2, 3, 1>(P, st);
+        case 51: return launch_patch_variant<1, 10, 14, 64, 3, 2, 2, 16, 2, 3, 1>(P, st);
+        case 52: return launch_patch_variant<0, 8, 16, 64, 4, 2, 3, 16, 0, 1, 1>(P, st);
+        case 53: return launch_patch_variant<1, 8, 16, 64, 4, 2, 3, 16, 0, 1, 1>(P, st);
+        case 54: return launch_patch_variant<0, 8, 16, 64, 4, 2, 2, 16, 0, 3, 1>(P, st);
+        case 55: return launch_patch_variant<1, 8, 16, 64, 4, 2, 2, 16, 0, 3, 1>(P, st);
         default: return hipErrorInvalidValue;
     }
 }

@@ -102,6 +102,7 @@ static bool patch_variant_ok(const Geom& g, bool dgrad, int v)
 {
     const PatchVariant& pv = kPatchVariants[v - 400];
     const int taps = g.R * g.S;
+    if (pv.one_slab && (dgrad ? g.K : g.C) != 64) return false;
     return patch_ok(g, dgrad) && taps % pv.tps == 0 && taps / pv.tps >= pv.stages - 1;
 }
 

@@ -23,7 +23,7 @@ import torch
 import paper_1903_05831_amd as sd
 from paper_1903_05831_amd import workloads
 
-FWD_DGRAD_VARIANTS = [101, 105, 107, 300, 303, 306, 310, 311, 312, 313, 314, 316, 317, 318, 319, 320, 321, 322, 323, 401, 403, 404, 408, 411, 412, 414, 415, 416, 417, 418, 419, 420, 421]
+FWD_DGRAD_VARIANTS = [101, 105, 107, 300, 303, 306, 310, 311, 312, 313, 314, 316, 317, 318, 319, 320, 321, 322, 323, 401, 403, 404, 408, 411, 412, 414, 415, 416, 417, 418, 419, 420, 421, 422, 423, 424, 425, 426, 427]
 WGRAD_VARIANTS = [100, 102, 104, 105, 107, 108, 109, 110, 112, 113, 114, 115, 116, 117, 118, 119, 120]
 WGRAD_SPLITS = [1, 2, 3, 4, 5, 6, 7, 8, 10, 12, 14, 16, 24, 32, 48, 64, 96, 128, 192, 256]
 HERE = os.path.dirname(os.path.abspath(__file__))
