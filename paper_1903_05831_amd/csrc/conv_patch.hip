@@ -9,10 +9,10 @@
 // slab (BN rows x 64 channels per tap) still streams through a ring, one stage per tap.
 // Activation traffic drops from 9x to (TH+2)(TW+2)/(TH*TW) = 1.27x (16x16) per slab.
 //
-// Roles: the upper half of the waves sends all loads (see igemm_ws.hip for why), every wave
-// multiplies.  Two patch buffers alternate between slabs; the patch of slab kc+1 is requested
-// at the first tap of slab kc and, because loads retire in order, has landed by the time the
-// filter stage of its first tap has.
+// Roles: either the upper half of the waves sends all loads (see igemm_ws.hip for why) and every
+// wave multiplies, or extra waves do nothing but fetch (NDW below).  Two patch buffers alternate
+// between slabs; the patch of slab kc+1 is requested at the first tap of slab kc and, because
+// loads retire in order, has landed by the time the filter stage of its first tap has.
 //
 // Valid for stride 1, (R-1)*dil_h == 2 and (S-1)*dil_w == 2 (3x3 dilation 1 in particular),
 // source channels a multiple of 64.  The data gradient of such a layer is the same kind of
@@ -43,12 +43,17 @@ typedef float float4p __attribute__((ext_vector_type(4)));
 // NPB: patch buffers.  Two alternate between channel slabs; a layer with 64 source channels has
 // one slab and needs one buffer, which lets two or three workgroups share a compute unit's LDS
 // (its 134 400-pixel maps make 546-1050 blocks: at one workgroup per unit they run in 3-4 rounds).
-template <int MODE, int TH, int TW, int BN, int WGM, int WGN, int SB, int MF = 32, int NIW = 0, int TPS = 1, int NPB = 2, bool TAIL = false>
-__global__ __launch_bounds__(64 * WGM * WGN) void conv_patch_kernel(IgemmParams P)
+// NDW: waves that only fetch, beside the WGM x WGN multiplying ones (then none of those fetches).
+// A wave stalls ~90 cycles in every LDS-DMA instruction it sends; with a dozen per step the
+// fetching waves of a small block reach the barrier a thousand cycles after the others
+// (timestamps of a 10 x 14 x 64 block: 1500 cycles of multiplying and 1200 of waiting per
+// step).  Waves with nothing else to do take the stalls off that path.
+template <int MODE, int TH, int TW, int BN, int WGM, int WGN, int SB, int MF = 32, int NIW = 0, int TPS = 1, int NPB = 2, int NDW = 0, bool TAIL = false>
+__global__ __launch_bounds__(64 * (WGM * WGN + NDW)) void conv_patch_kernel(IgemmParams P)
 {
     constexpr int EH = 2, EW = 2;                   // extra patch rows / columns
     constexpr int PH = TH + EH, PW = TW + EW, PPX = PH * PW;
-    constexpr int NW = WGM * WGN, NI = NIW ? NIW : NW / 2, IW0 = NW - NI;
+    constexpr int NW = WGM * WGN, NI = NDW ? NDW : (NIW ? NIW : NW / 2), IW0 = NDW ? NW : NW - NI;
     constexpr int BM = TH * TW;                             // output pixels of the block
     constexpr int BMP = (BM + MF * WGM - 1) / (MF * WGM) * (MF * WGM);   // GEMM rows incl. padding
     constexpr int WM = BMP / WGM, WN = BN / WGN;
@@ -61,7 +66,7 @@ __global__ __launch_bounds__(64 * WGM * WGN) void conv_patch_kernel(IgemmParams 
     constexpr int BSLAB = BN * 128;                        // one tap's filter slab
     constexpr int BSTAGE = TPS * BSLAB;
     constexpr int D = SB - 1;                              // filter stages in flight
-    static_assert((MF == 32 || MF == 16) && NI >= 1 && NI < NW && WM % MF == 0 && WN % MF == 0 && BN % (8 * NI) == 0, "tile shape");
+    static_assert((MF == 32 || MF == 16) && NI >= 1 && (NDW > 0 || NI < NW) && WM % MF == 0 && WN % MF == 0 && BN % (8 * NI) == 0, "tile shape");
     static_assert(SB >= 2 && NPL + D * PB < 64, "loads in flight");   // vmcnt is a 6-bit counter
     static_assert(NPB == 1 || NPB == 2, "patch buffers");
 
@@ -243,7 +248,7 @@ __global__ __launch_bounds__(64 * WGM * WGN) void conv_patch_kernel(IgemmParams 
             if (tap == 0 && kc + 1 < kchunks) issue_patch(kc + 1);   // its buffer was last read in slab kc-1
             if (t + D < nk) issue_filter();
         }
-        compute(kc, tap, stage);
+        if (NDW == 0 || wave < NW) compute(kc, tap, stage);
         stage = (stage + 1 == SB) ? 0 : stage + 1;
         if (++tap == ngroups) { tap = 0; ++kc; }
     }
@@ -252,6 +257,7 @@ __global__ __launch_bounds__(64 * WGM * WGN) void conv_patch_kernel(IgemmParams 
     static_assert(NW * epilogue_strip_bytes<WN, MF>() <= NPB * PATCHB + SB * TPS * BN * 128,
                   "epilogue strips fit in the patch buffers and the filter ring");
     __builtin_amdgcn_s_barrier();                   // everybody is done reading the last patch and filter stage
+    if (NDW > 0 && wave >= NW) return;              // no barrier follows
     store_rows_via_lds<FM, FN, MF, TAIL>(acc, smem + wave * epilogue_strip_bytes<WN, MF>(), lane, n0 + wn * WN, P,
                                [&](int r) -> long {
         const int ml = wm * WM + r;
@@ -261,34 +267,34 @@ __global__ __launch_bounds__(64 * WGM * WGN) void conv_patch_kernel(IgemmParams 
     });
 }
 
-template <int MODE, int TH, int TW, int BN, int WGM, int WGN, int SB, int MF = 32, int NIW = 0, int TPS = 1, int NPB = 2, bool TAIL>
+template <int MODE, int TH, int TW, int BN, int WGM, int WGN, int SB, int MF = 32, int NIW = 0, int TPS = 1, int NPB = 2, int NDW = 0, bool TAIL>
 static hipError_t launch_patch_variant_impl(const IgemmParams& P, hipStream_t st)
 {
     if ((P.R * P.S) % TPS != 0 || (P.R * P.S) / TPS < SB - 1) return hipErrorInvalidValue;
     if (NPB == 1 && P.Cs != 64) return hipErrorInvalidValue;      // one patch buffer = one channel slab
-    constexpr int NI = NIW ? NIW : WGM * WGN / 2;
+    constexpr int NI = NDW ? NDW : (NIW ? NIW : WGM * WGN / 2);
     constexpr int NPL = ((TH + 2) * (TW + 2) + 8 * NI - 1) / (8 * NI);
     constexpr size_t lds = (size_t)NPB * NPL * NI * 1024 + (size_t)SB * TPS * BN * 128 + 2 * kMaxTaps * sizeof(int);
     static_assert(lds <= 160 * 1024, "LDS budget");
     static bool configured = false;
     if (!configured) {
         hipError_t e = hipFuncSetAttribute(
-            reinterpret_cast<const void*>(&conv_patch_kernel<MODE, TH, TW, BN, WGM, WGN, SB, MF, NIW, TPS, NPB, TAIL>),
+            reinterpret_cast<const void*>(&conv_patch_kernel<MODE, TH, TW, BN, WGM, WGN, SB, MF, NIW, TPS, NPB, NDW, TAIL>),
             hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         if (e != hipSuccess) return e;
         configured = true;
     }
     const int grid = ((P.total_tiles + 63) / 64) * 64;
-    hipLaunchKernelGGL((conv_patch_kernel<MODE, TH, TW, BN, WGM, WGN, SB, MF, NIW, TPS, NPB, TAIL>), dim3(grid), dim3(64 * WGM * WGN),
+    hipLaunchKernelGGL((conv_patch_kernel<MODE, TH, TW, BN, WGM, WGN, SB, MF, NIW, TPS, NPB, NDW, TAIL>), dim3(grid), dim3(64 * (WGM * WGN + NDW)),
                        lds, st, P);
     return hipGetLastError();
 }
 
-template <int MODE, int TH, int TW, int BN, int WGM, int WGN, int SB, int MF = 32, int NIW = 0, int TPS = 1, int NPB = 2>
+template <int MODE, int TH, int TW, int BN, int WGM, int WGN, int SB, int MF = 32, int NIW = 0, int TPS = 1, int NPB = 2, int NDW = 0>
 static hipError_t launch_patch_variant(const IgemmParams& P, hipStream_t st)
 {
     // the tail has kernels of its own: see store_rows_via_lds
-    return P.ep.any() ? launch_patch_variant_impl<MODE, TH, TW, BN, WGM, WGN, SB, MF, NIW, TPS, NPB, true>(P, st) : launch_patch_variant_impl<MODE, TH, TW, BN, WGM, WGN, SB, MF, NIW, TPS, NPB, false>(P, st);
+    return P.ep.any() ? launch_patch_variant_impl<MODE, TH, TW, BN, WGM, WGN, SB, MF, NIW, TPS, NPB, NDW, true>(P, st) : launch_patch_variant_impl<MODE, TH, TW, BN, WGM, WGN, SB, MF, NIW, TPS, NPB, NDW, false>(P, st);
 }
 
 const PatchVariant kPatchVariants[kNumPatchVariants] = {
@@ -321,6 +327,15 @@ const PatchVariant kPatchVariants[kNumPatchVariants] = {
     {10, 14, 64, 3, 2, "conv_fwd_patch_10x14x64_6w_s2_m16_t3_1p", "conv_dgrad_patch_10x14x64_6w_s2_m16_t3_1p", 1},
     {8, 16, 64, 1, 3, "conv_fwd_patch_8x16x64_s3_m16_1p", "conv_dgrad_patch_8x16x64_s3_m16_1p", 1},
     {8, 16, 64, 3, 2, "conv_fwd_patch_8x16x64_s2_m16_t3_1p", "conv_dgrad_patch_8x16x64_s2_m16_t3_1p", 1},
+    // waves that only fetch beside the multiplying ones
+    {10, 14, 64, 3, 4, "conv_fwd_patch_10x14x64_6w2f_s4_m16_t3", "conv_dgrad_patch_10x14x64_6w2f_s4_m16_t3"},
+    {10, 14, 64, 3, 3, "conv_fwd_patch_10x14x64_6w2f_s3_m16_t3", "conv_dgrad_patch_10x14x64_6w2f_s3_m16_t3"},
+    {10, 14, 128, 3, 2, "conv_fwd_patch_10x14x128_12w4f_s2_m16_t3", "conv_dgrad_patch_10x14x128_12w4f_s2_m16_t3"},
+    {10, 14, 128, 3, 2, "conv_fwd_patch_10x14x128_6w2f_s2_m16_t3", "conv_dgrad_patch_10x14x128_6w2f_s2_m16_t3"},
+    {16, 16, 64, 3, 2, "conv_fwd_patch_16x16x64_8w2f_s2_m16_t3", "conv_dgrad_patch_16x16x64_8w2f_s2_m16_t3"},
+    {10, 14, 64, 3, 2, "conv_fwd_patch_10x14x64_6w2f_s2_m16_t3_1p", "conv_dgrad_patch_10x14x64_6w2f_s2_m16_t3_1p", 1},
+    {10, 14, 64, 1, 3, "conv_fwd_patch_10x14x64_6w2f_s3_m16_1p", "conv_dgrad_patch_10x14x64_6w2f_s3_m16_1p", 1},
+    {10, 14, 64, 3, 4, "conv_fwd_patch_10x14x64_6w4f_s4_m16_t3", "conv_dgrad_patch_10x14x64_6w4f_s4_m16_t3"},
 };
 
 #define SDCONV_PATCH_CASE(idx, TH, TW, BN, WGM, WGN, SB)                                      \
@@ -381,6 +396,22 @@ hipError_t launch_conv_patch(int variant, const IgemmParams& P, hipStream_t st)
         case 53: return launch_patch_variant<1, 8, 16, 64, 4, 2, 3, 16, 0, 1, 1>(P, st);
         case 54: return launch_patch_variant<0, 8, 16, 64, 4, 2, 2, 16, 0, 3, 1>(P, st);
         case 55: return launch_patch_variant<1, 8, 16, 64, 4, 2, 2, 16, 0, 3, 1>(P, st);
+        case 56: return launch_patch_variant<0, 10, 14, 64, 3, 2, 4, 16, 0, 3, 2, 2>(P, st);
+        case 57: return launch_patch_variant<1, 10, 14, 64, 3, 2, 4, 16, 0, 3, 2, 2>(P, st);
+        case 58: return launch_patch_variant<0, 10, 14, 64, 3, 2, 3, 16, 0, 3, 2, 2>(P, st);
+        case 59: return launch_patch_variant<1, 10, 14, 64, 3, 2, 3, 16, 0, 3, 2, 2>(P, st);
+        case 60: return launch_patch_variant<0, 10, 14, 128, 3, 4, 2, 16, 0, 3, 2, 4>(P, st);
+        case 61: return launch_patch_variant<1, 10, 14, 128, 3, 4, 2, 16, 0, 3, 2, 4>(P, st);
+        case 62: return launch_patch_variant<0, 10, 14, 128, 3, 2, 2, 16, 0, 3, 2, 2>(P, st);
+        case 63: return launch_patch_variant<1, 10, 14, 128, 3, 2, 2, 16, 0, 3, 2, 2>(P, st);
+        case 64: return launch_patch_variant<0, 16, 16, 64, 4, 2, 2, 16, 0, 3, 2, 2>(P, st);
+        case 65: return launch_patch_variant<1, 16, 16, 64, 4, 2, 2, 16, 0, 3, 2, 2>(P, st);
+        case 66: return launch_patch_variant<0, 10, 14, 64, 3, 2, 2, 16, 0, 3, 1, 2>(P, st);
+        case 67: return launch_patch_variant<1, 10, 14, 64, 3, 2, 2, 16, 0, 3, 1, 2>(P, st);
+        case 68: return launch_patch_variant<0, 10, 14, 64, 3, 2, 3, 16, 0, 1, 1, 2>(P, st);
+        case 69: return launch_patch_variant<1, 10, 14, 64, 3, 2, 3, 16, 0, 1, 1, 2>(P, st);
+        case 70: return launch_patch_variant<0, 10, 14, 64, 3, 2, 4, 16, 0, 3, 2, 4>(P, st);
+        case 71: return launch_patch_variant<1, 10, 14, 64, 3, 2, 4, 16, 0, 3, 2, 4>(P, st);
         default: return hipErrorInvalidValue;
     }
 }

@@ -133,7 +133,8 @@ static int pick_variant(const Geom& g, bool dgrad)
     const long covered = (long)((Hd + 9) / 10) * 10 * ((Wd + 13) / 14) * 14;
     const bool blocks_fill = covered * 2 <= (long)Hd * Wd * 3;      // at most 1.5x the pixels
     if (blocks_fill && nout >= 128 && rows >= 20000 && patch_variant_ok(g, dgrad, 415)) return 415;
-    if (blocks_fill && patch_variant_ok(g, dgrad, dgrad ? 414 : 419)) return dgrad ? 414 : 419;
+    if (blocks_fill && (dgrad ? g.K : g.C) == 64 && patch_variant_ok(g, dgrad, 433)) return 433;
+    if (blocks_fill && patch_variant_ok(g, dgrad, 429)) return 429;
     // narrow outputs: 64-wide tiles
     if (nout <= 64) return 100 + 7;
     // enough rows to fill the chip with 224-row tiles: the big tile for long contractions and wide

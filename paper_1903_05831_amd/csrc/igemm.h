@@ -40,7 +40,7 @@ hipError_t launch_igemm_ws(int variant, const IgemmParams& P, hipStream_t st);
 struct PatchVariant { int th, tw, bn, tps, stages; const char* fwd_name; const char* dgrad_name; int one_slab = 0; };
 // tps: taps per pipeline step, must divide R*S, and R*S/tps must be at least stages-1;
 // one_slab: the variant has a single patch buffer and takes layers with 64 source channels only
-constexpr int kNumPatchVariants = 28;
+constexpr int kNumPatchVariants = 36;
 extern const PatchVariant kPatchVariants[kNumPatchVariants];
 hipError_t launch_conv_patch(int variant, const IgemmParams& P, hipStream_t st);
 hipError_t launch_igemm(int variant, const IgemmParams& P, int total_tiles, hipStream_t st);

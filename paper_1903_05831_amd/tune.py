@@ -23,7 +23,9 @@ import torch
 import paper_1903_05831_amd as sd
 from paper_1903_05831_amd import workloads
 
-FWD_DGRAD_VARIANTS = [101, 105, 107, 300, 303, 306, 310, 311, 312, 313, 314, 316, 317, 318, 319, 320, 321, 322, 323, 401, 403, 404, 408, 411, 412, 414, 415, 416, 417, 418, 419, 420, 421, 422, 423, 424, 425, 426, 427]
+FWD_DGRAD_VARIANTS = [101, 105, 107, 300, 303, 306, 310, 311, 312, 313, 314, 316, 317, 318, 319, 320, 321, 322, 323, 401, 403, 404, 408, 411, 412, 414, 415, 416, 417, 418, 419, 420, 421, 422, 423, 424, 425, 426, 427, 428, 429, 430, 431, 432, 433, 434, 435]
+# patch variants with a single patch buffer (the dispatcher hands them layers with 64 contraction channels only)
+ONE_SLAB_VARIANTS = {422, 423, 424, 425, 426, 427, 433, 434}
 WGRAD_VARIANTS = [100, 102, 104, 105, 107, 108, 109, 110, 112, 113, 114, 115, 116, 117, 118, 119, 120]
 WGRAD_SPLITS = [1, 2, 3, 4, 5, 6, 7, 8, 10, 12, 14, 16, 24, 32, 48, 64, 96, 128, 192, 256]
 HERE = os.path.dirname(os.path.abspath(__file__))
@@ -136,6 +138,8 @@ def main() -> int:
                     os.environ["SDCONV_IGEMM_VARIANT"] = str(v)
                     if v >= 400 and "patch" not in sd.kernel_name(d, pid):
                         continue        # the patch kernels take stride-1 3x3-class layers only
+                    if v in ONE_SLAB_VARIANTS and (l.C if pid == sd.FWD else l.K) != 64:
+                        continue        # one patch buffer: a single 64-channel slab on the contraction side
                     ws = torch.empty(max(sd.conv2d_workspace_bytes(d, pid), 256), dtype=torch.uint8, device=dev)
                     if pid == sd.FWD:
                         fn = lambda i: sd.conv2d_fwd(d, xs[i], wts[i], y, ws, st)

@@ -51,12 +51,13 @@ PATCH_SHAPES = [
     (1, 16, 16, 64, 64, 2, 2, (1, 1), (1, 1), (2, 2)),      # 2x2 taps, dilation 2
     (1, 9, 40, 64, 64, 3, 2, (1, 1), (1, 1), (1, 2)),       # 3x2 taps, dilation 1x2
 ]
-PATCH_VARIANTS = list(range(400, 428))
+PATCH_VARIANTS = list(range(400, 436))
 # these take three taps per pipeline step: R*S must be a multiple of 3 and give at least
 # (ring stages - 1) steps per channel slab; variant -> ring stages
-THREE_TAP_STEP = {414: 3, 415: 2, 416: 2, 417: 2, 418: 3, 419: 4, 420: 3, 421: 2, 423: 2, 425: 2, 427: 2}
+THREE_TAP_STEP = {414: 3, 415: 2, 416: 2, 417: 2, 418: 3, 419: 4, 420: 3, 421: 2, 423: 2, 425: 2, 427: 2,
+                  428: 4, 429: 3, 430: 2, 431: 2, 432: 2, 433: 2, 435: 4}
 # these have a single patch buffer: one 64-channel slab on the contraction side of both passes
-ONE_SLAB = set(range(422, 428))
+ONE_SLAB = set(range(422, 428)) | {433, 434}
 
 
 @pytest.mark.parametrize("variant", PATCH_VARIANTS)
