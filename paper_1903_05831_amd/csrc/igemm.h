@@ -31,7 +31,7 @@ struct IgemmVariant { int bm, bn; const char* fwd_name; const char* dgrad_name; 
 constexpr int kNumIgemmVariants = 4;
 extern const IgemmVariant kIgemmVariants[kNumIgemmVariants];
 
-constexpr int kNumIgemmDmaVariants = 12;
+constexpr int kNumIgemmDmaVariants = 14;
 extern const IgemmVariant kIgemmDmaVariants[kNumIgemmDmaVariants];
 hipError_t launch_igemm_dma(int variant, const IgemmParams& P, hipStream_t st);
 constexpr int kNumIgemmWsVariants = 24;

@@ -277,6 +277,10 @@ const IgemmVariant kIgemmDmaVariants[kNumIgemmDmaVariants] = {
     {256, 256, "igemm_fwd_dma_256x256x32_8w_s3", "igemm_dgrad_dma_256x256x32_8w_s3"},
     {256, 256, "igemm_fwd_dma_256x256x32_8w_s4", "igemm_dgrad_dma_256x256x32_8w_s4"},
     {256, 256, "igemm_fwd_dma_256x256x32_8w_s4_w64x128", "igemm_dgrad_dma_256x256x32_8w_s4_w64x128"},
+    // shallower rings of the 128x64 tile: more workgroups per compute unit for the HBM-bound
+    // 1x1 layers of res2, whose contraction is two to eight steps long
+    {128, 64, "igemm_fwd_dma_128x64x32_4w_s2", "igemm_dgrad_dma_128x64x32_4w_s2"},
+    {128, 64, "igemm_fwd_dma_128x64x32_4w_s3", "igemm_dgrad_dma_128x64x32_4w_s3"},
 };
 
 #define SDCONV_DMA_CASE(idx, BM, BN, WGM, WGN, S, BK)                                         \
@@ -299,6 +303,8 @@ hipError_t launch_igemm_dma(int variant, const IgemmParams& P, hipStream_t st)
         SDCONV_DMA_CASE(9, 256, 256, 2, 4, 3, 32)
         SDCONV_DMA_CASE(10, 256, 256, 2, 4, 4, 32)
         SDCONV_DMA_CASE(11, 256, 256, 4, 2, 4, 32)
+        SDCONV_DMA_CASE(12, 128, 64, 2, 2, 2, 32)
+        SDCONV_DMA_CASE(13, 128, 64, 2, 2, 3, 32)
         default: return hipErrorInvalidValue;
     }
 }

@@ -94,9 +94,9 @@ def test_split_role_kernel_variants(variant):
             check_all_passes(d, x, w, g, f"ws{variant}{case}")
 
 
-# the kernels in which every wave fetches its own share (igemm_dma.hip, 100-111) and the
+# the kernels in which every wave fetches its own share (igemm_dma.hip, 100-113) and the
 # register-staged ones (igemm.hip, 0-3); their data gradient takes a transposed filter copy
-DMA_VARIANTS = [0, 1, 2, 3] + list(range(100, 112))
+DMA_VARIANTS = [0, 1, 2, 3] + list(range(100, 114))
 
 
 @pytest.mark.parametrize("variant", DMA_VARIANTS)
