@@ -112,6 +112,14 @@ static const char* igemm_name(int v, bool dgrad)
     return dgrad ? igemm_variant(v).dgrad_name : igemm_variant(v).fwd_name;
 }
 
+// The launch with two tile widths (324) takes undivided images only: a strided data gradient
+// with its parity classes runs as the plain 224 x 256 variant.
+static int ws_variant_for(const Geom& g, bool dgrad, int v)
+{
+    if (v == 324 && dgrad && g.sh * g.sw > 1) return 310;
+    return v;
+}
+
 static int pick_variant(const Geom& g, bool dgrad)
 {
     int fv = forced_variant();
@@ -119,9 +127,9 @@ static int pick_variant(const Geom& g, bool dgrad)
     if (fv >= 400) fv = -1;
     if (fv >= 0 && fv < kNumIgemmVariants) return fv;
     if (fv >= 100 && fv < 100 + kNumIgemmDmaVariants) return fv;
-    if (fv >= 300 && fv < 300 + kNumIgemmWsVariants) return fv;
+    if (fv >= 300 && fv < 300 + kNumIgemmWsVariants) return ws_variant_for(g, dgrad, fv);
     if (const TunedEntry* e = tuned_lookup(g, dgrad ? SDCONV_DGRAD : SDCONV_FWD))
-        if (e->variant < 400 || patch_variant_ok(g, dgrad, e->variant)) return e->variant;
+        if (e->variant < 400 || patch_variant_ok(g, dgrad, e->variant)) return ws_variant_for(g, dgrad, e->variant);
     // No table entry: rules read off the tuned layers of the detector workloads.
     const int nout = dgrad ? g.C : g.K;
     const int kgemm = g.R * g.S * (dgrad ? g.K : g.C);

@@ -24,6 +24,9 @@ struct IgemmParams {
     int b_row_pitch;   // R*S*Cs
     int class_tile_start[kMaxClasses + 1];   // first row-tile of each class, then the total
     int tiles_h, tiles_w;   // spatial tiles per image (patch kernels only)
+    // launches with two tile widths (igemm_ws_mixed_kernel; set by its launcher)
+    int mix_big_tiles, mix_big_blocks;                        // wide tiles, and the workgroups that cover them
+    int mix_small_tiles, mix_small_tiles_n, mix_small_tm0;    // narrow tiles: count, per row tile, first row tile
     Epilogue ep;            // elementwise tail before the rounding to binary16 (all null: none)
 };
 
@@ -34,7 +37,7 @@ extern const IgemmVariant kIgemmVariants[kNumIgemmVariants];
 constexpr int kNumIgemmDmaVariants = 14;
 extern const IgemmVariant kIgemmDmaVariants[kNumIgemmDmaVariants];
 hipError_t launch_igemm_dma(int variant, const IgemmParams& P, hipStream_t st);
-constexpr int kNumIgemmWsVariants = 24;
+constexpr int kNumIgemmWsVariants = 25;
 extern const IgemmVariant kIgemmWsVariants[kNumIgemmWsVariants];
 hipError_t launch_igemm_ws(int variant, const IgemmParams& P, hipStream_t st);
 struct PatchVariant { int th, tw, bn, tps, stages; const char* fwd_name; const char* dgrad_name; int one_slab = 0; };

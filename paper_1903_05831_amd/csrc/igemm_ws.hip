@@ -37,8 +37,10 @@ typedef float float4v_ __attribute__((ext_vector_type(4)));
 // MF: 32 = v_mfma_f32_32x32x16_f16 blocks; 16 = v_mfma_f32_16x16x32_f16 blocks, for tile heights
 // that are a multiple of 16 but not of 32 per wave row (224 = 2 x 112 rows: 25088 = 112 x 224
 // pixels of the RoI head then give 224 or 896 tiles instead of 196 or 784 for 256 CUs).
+// The work of one workgroup on tile `tile` of a launch (or of a part of one, see
+// igemm_ws_mixed_kernel) with `tiles_n` column tiles whose row tiles start at row tile `tm0`.
 template <int MODE, int BM, int BN, int WGM, int WGN, int S, int BK, int NP, int MF = 32, bool TAIL = false>
-__global__ __launch_bounds__(64 * (WGM * WGN + NP)) void igemm_ws_kernel(IgemmParams P)
+__device__ __forceinline__ void igemm_ws_body(const IgemmParams& P, const int tile, const int tiles_n, const int tm0)
 {
     constexpr int NWC = WGM * WGN;                  // multiplying waves
     constexpr int NW = NWC + NP, NT = 64 * NW;
@@ -75,13 +77,8 @@ __global__ __launch_bounds__(64 * (WGM * WGN + NP)) void igemm_ws_kernel(IgemmPa
     const int lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
 
-    // ---- which tile (runs of 8 consecutive tiles per XCD, runs interleaved over the XCDs) ----
-    constexpr int kRun = 8;
-    const int xcd = blockIdx.x & 7, idx = blockIdx.x >> 3;
-    const int tile = ((idx / kRun) * 8 + xcd) * kRun + (idx % kRun);
-    if (tile >= P.total_tiles) return;
-    const int tn = tile % P.tiles_n;
-    int tm = tile / P.tiles_n;
+    const int tn = tile % tiles_n;
+    int tm = tile / tiles_n + tm0;
     int cls = 0;
     while (cls + 1 < P.nclasses && tm >= P.class_tile_start[cls + 1]) ++cls;
     tm -= P.class_tile_start[cls];
@@ -322,6 +319,84 @@ __global__ __launch_bounds__(64 * (WGM * WGN + NP)) void igemm_ws_kernel(IgemmPa
                                Mcls, P, Hi, Wj, eh, ew, ca, cb);
 }
 
+// Which tile a workgroup takes: runs of 8 consecutive tiles per XCD (workgroup b runs on XCD
+// b % 8), runs interleaved over the XCDs.
+__device__ __forceinline__ int xcd_run_tile(int b)
+{
+    constexpr int kRun = 8;
+    const int xcd = b & 7, idx = b >> 3;
+    return ((idx / kRun) * 8 + xcd) * kRun + (idx % kRun);
+}
+
+template <int MODE, int BM, int BN, int WGM, int WGN, int S, int BK, int NP, int MF = 32, bool TAIL = false>
+__global__ __launch_bounds__(64 * (WGM * WGN + NP)) void igemm_ws_kernel(IgemmParams P)
+{
+    const int tile = xcd_run_tile(blockIdx.x);
+    if (tile >= P.total_tiles) return;
+    igemm_ws_body<MODE, BM, BN, WGM, WGN, S, BK, NP, MF, TAIL>(P, tile, P.tiles_n, 0);
+}
+
+// Two tile widths in one launch.  A layer whose tiles make a few whole rounds of the chip's
+// compute units plus half a round (896 tiles of 224 x 256 on 256 CUs: the 1x1 layers of the RoI
+// head) leaves half the units idle for the last round.  Here the first mix_big_tiles tiles are
+// BN wide and the row tiles after them are cut into tiles of half the width, twice as many and
+// ~0.64 of the time each, so the last round fills the chip.  Undivided images only (one parity
+// class); both bodies have the same waves.
+template <int MODE, int BM, int BN, int BNS, int WGM, int WGN, int S, int SS, int BK, int MF, bool TAIL>
+__global__ __launch_bounds__(64 * WGM * WGN) void igemm_ws_mixed_kernel(IgemmParams P)
+{
+    int b = blockIdx.x;
+    if (b < P.mix_big_blocks) {
+        const int tile = xcd_run_tile(b);
+        if (tile >= P.mix_big_tiles) return;
+        igemm_ws_body<MODE, BM, BN, WGM, WGN, S, BK, 0, MF, TAIL>(P, tile, P.tiles_n, 0);
+    } else {
+        const int tile = xcd_run_tile(b - P.mix_big_blocks);
+        if (tile >= P.mix_small_tiles) return;
+        igemm_ws_body<MODE, BM, BNS, WGM, WGN, SS, BK, 0, MF, TAIL>(P, tile, P.mix_small_tiles_n, P.mix_small_tm0);
+    }
+}
+
+template <int MODE, int BM, int BN, int BNS, int WGM, int WGN, int S, int SS, int BK, int MF, bool TAIL>
+static hipError_t launch_ws_mixed_impl(const IgemmParams& P0, hipStream_t st)
+{
+    constexpr size_t lds_big = (size_t)S * (BM + BN) * BK * 2, lds_small = (size_t)SS * (BM + BNS) * BK * 2;
+    constexpr size_t lds = (lds_big > lds_small ? lds_big : lds_small) + (4 * kMaxTaps + 4) * sizeof(int) + (size_t)BM * 12;
+    static_assert(lds <= 160 * 1024, "LDS budget");
+    if (P0.nclasses != 1) return hipErrorInvalidValue;
+    static bool configured = false;
+    if (!configured) {
+        hipError_t e = hipFuncSetAttribute(
+            reinterpret_cast<const void*>(&igemm_ws_mixed_kernel<MODE, BM, BN, BNS, WGM, WGN, S, SS, BK, MF, TAIL>),
+            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        if (e != hipSuccess) return e;
+        configured = true;
+    }
+    // P0.tiles_n / P0.total_tiles describe the launch in BN-wide tiles.  Whole rounds of 256
+    // workgroups stay BN wide (rounded down to whole row tiles); the rest is cut in two.
+    IgemmParams P = P0;
+    const int row_tiles = P0.total_tiles / P0.tiles_n;
+    int big_rows = (P0.total_tiles / 256 * 256) / P0.tiles_n;
+    if (2 * (P0.total_tiles % 256) > 256 + P0.tiles_n) big_rows = row_tiles;     // the half tiles would need two rounds
+    P.mix_big_tiles = big_rows * P0.tiles_n;
+    P.mix_big_blocks = (P.mix_big_tiles + 63) / 64 * 64;
+    P.mix_small_tm0 = big_rows;
+    P.mix_small_tiles_n = (P0.Cd + BNS - 1) / BNS;
+    P.mix_small_tiles = (row_tiles - big_rows) * P.mix_small_tiles_n;
+    const int grid = P.mix_big_blocks + (P.mix_small_tiles + 63) / 64 * 64;
+    if (grid == 0) return hipSuccess;
+    hipLaunchKernelGGL((igemm_ws_mixed_kernel<MODE, BM, BN, BNS, WGM, WGN, S, SS, BK, MF, TAIL>), dim3(grid),
+                       dim3(64 * WGM * WGN), lds, st, P);
+    return hipGetLastError();
+}
+
+template <int MODE, int BM, int BN, int BNS, int WGM, int WGN, int S, int SS, int BK, int MF>
+static hipError_t launch_ws_mixed(const IgemmParams& P, hipStream_t st)
+{
+    return P.ep.any() ? launch_ws_mixed_impl<MODE, BM, BN, BNS, WGM, WGN, S, SS, BK, MF, true>(P, st)
+                      : launch_ws_mixed_impl<MODE, BM, BN, BNS, WGM, WGN, S, SS, BK, MF, false>(P, st);
+}
+
 template <int MODE, int BM, int BN, int WGM, int WGN, int S, int BK, int NP, int MF = 32, bool TAIL>
 static hipError_t launch_ws_variant_impl(const IgemmParams& P, hipStream_t st)
 {
@@ -373,6 +448,7 @@ const IgemmVariant kIgemmWsVariants[kNumIgemmWsVariants] = {
     {144, 128, "igemm_fwd_ws_144x128x64_6w2f_s3_m16", "igemm_dgrad_ws_144x128x64_6w2f_s3_m16"},
     {144, 256, "igemm_fwd_ws_144x256x64_6w2f_s2_m16", "igemm_dgrad_ws_144x256x64_6w2f_s2_m16"},
     {144, 64, "igemm_fwd_ws_144x64x64_3w2f_s4_m16", "igemm_dgrad_ws_144x64x64_3w2f_s4_m16"},
+    {224, 256, "igemm_fwd_ws_224x256x64_8w0f_s2_m16_tail128", "igemm_dgrad_ws_224x256x64_8w0f_s2_m16_tail128"},
 };
 
 #define SDCONV_WS_CASE(idx, BM, BN, WGM, WGN, S, BK, NP)                                      \
@@ -426,6 +502,9 @@ hipError_t launch_igemm_ws(int variant, const IgemmParams& P, hipStream_t st)
         case 45: return launch_ws_variant<1, 144, 256, 3, 2, 2, 64, 2, 16>(P, st);
         case 46: return launch_ws_variant<0, 144, 64, 3, 1, 4, 64, 2, 16>(P, st);
         case 47: return launch_ws_variant<1, 144, 64, 3, 1, 4, 64, 2, 16>(P, st);
+        // 224 x 256 tiles for the whole rounds of 256 workgroups, 224 x 128 for the rest
+        case 48: return launch_ws_mixed<0, 224, 256, 128, 2, 4, 2, 3, 64, 16>(P, st);
+        case 49: return launch_ws_mixed<1, 224, 256, 128, 2, 4, 2, 3, 64, 16>(P, st);
         default: return hipErrorInvalidValue;
     }
 }

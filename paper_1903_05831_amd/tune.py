@@ -23,7 +23,7 @@ import torch
 import paper_1903_05831_amd as sd
 from paper_1903_05831_amd import workloads
 
-FWD_DGRAD_VARIANTS = [101, 105, 107, 112, 113, 300, 303, 306, 310, 311, 312, 313, 314, 316, 317, 318, 319, 320, 321, 322, 323, 401, 403, 404, 408, 411, 412, 414, 415, 416, 417, 418, 419, 420, 421, 422, 423, 424, 425, 426, 427, 428, 429, 430, 431, 432, 433, 434, 435]
+FWD_DGRAD_VARIANTS = [101, 105, 107, 112, 113, 300, 303, 306, 310, 311, 312, 313, 314, 316, 317, 318, 319, 320, 321, 322, 323, 324, 401, 403, 404, 408, 411, 412, 414, 415, 416, 417, 418, 419, 420, 421, 422, 423, 424, 425, 426, 427, 428, 429, 430, 431, 432, 433, 434, 435]
 # patch variants with a single patch buffer (the dispatcher hands them layers with 64 contraction channels only)
 ONE_SLAB_VARIANTS = {422, 423, 424, 425, 426, 427, 433, 434}
 WGRAD_VARIANTS = [100, 102, 104, 105, 107, 108, 109, 110, 112, 113, 114, 115, 116, 117, 118, 119, 120]

@@ -81,7 +81,7 @@ WS_SHAPES = [
     (1, 31, 37, 136, 200, 3, 3, (1, 1), (1, 1), (1, 1)),    # short last channel slab, filter tail
     (1, 31, 37, 128, 264, 1, 1, (1, 1), (0, 0), (1, 1)),    # 1x1, more than one 256-wide column tile
 ]
-WS_VARIANTS = list(range(300, 324))
+WS_VARIANTS = list(range(300, 325))
 
 
 @pytest.mark.parametrize("variant", WS_VARIANTS)
@@ -92,6 +92,18 @@ def test_split_role_kernel_variants(variant):
         with forced(SDCONV_IGEMM_VARIANT=variant, SDCONV_NO_TUNED_TABLE=1):
             assert "_ws_" in sd.kernel_name(d, sd.FWD)
             check_all_passes(d, x, w, g, f"ws{variant}{case}")
+
+
+def test_two_tile_widths_in_one_launch():
+    """Variant 324 on a layer with 71 x 4 tiles of 224 x 256 (15 700 = 70 x 224 + 20 rows, so the
+    last row tile is ragged): 256 of them stay that wide, the last seven row tiles are cut into 56
+    tiles of 224 x 128; the data gradient of the same layer has 71 x 1 tiles and runs them all half
+    as wide."""
+    case = (1, 100, 157, 64, 1024, 1, 1, (1, 1), (0, 0), (1, 1))
+    d, x, w, g = _rand_case(*case, seed=324)
+    with forced(SDCONV_IGEMM_VARIANT=324, SDCONV_NO_TUNED_TABLE=1):
+        assert "tail128" in sd.kernel_name(d, sd.FWD)
+        check_all_passes(d, x, w, g, f"mixed{case}")
 
 
 # the kernels in which every wave fetches its own share (igemm_dma.hip, 100-113) and the
