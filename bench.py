@@ -275,25 +275,37 @@ def main() -> int:
     unscale_ms = sum(ev[s][-1][0].elapsed_time(ev[s][-1][1]) for s in range(args.steps)) / args.steps
     instrumented_ms = sum(g["ms"] for g in groups.values()) + unscale_ms
 
-    # dominant kernel: largest share of the step among single-kernel calls (forward launches
-    # are exactly one kernel per event pair)
-    fwd_groups = {k: g for k, g in groups.items() if g["pass"] == "fwd"}
-    dom_name, dom = max(fwd_groups.items(), key=lambda kv: kv[1]["ms"])
-    dom_avg_ms = dom["ms"] / dom["launches"]
-    dom_flops = dom["flops"] / dom["launches"]
-    achieved = dom_flops / dom_avg_ms / 1e9
-    roofline = {"kernel": dom_name, "bound": "mfma", "achieved": achieved, "peak": PEAK_F16_TFLOPS,
-                "unit": "TFLOP/s", "frac": achieved / PEAK_F16_TFLOPS, "traffic": None,
-                "avg_launch_us": dom_avg_ms * 1e3, "launches_per_step": dom["launches"],
-                "flop_per_launch": dom_flops, "algorithmic_bytes_per_launch": dom["bytes"] / dom["launches"]}
+    # dominant kernel: largest share of the step among the calls that are exactly one kernel per
+    # event pair: every forward call but the stem's, and the data-gradient calls of the split-role
+    # and patch kernels (the older data-gradient path and the weight gradient launch a filter copy
+    # or a reduction beside their main kernel)
+    def single_kernel(name, g):
+        if g["pass"] == "fwd":
+            return not name.startswith(("thin", "padk"))
+        return g["pass"] == "dgrad" and ("_ws_" in name or "patch" in name) and not name.startswith("padk")
     try:
         with open(args.traffic_file) as f:
-            tr = json.load(f)
-        if tr.get("kernel") == dom_name:
-            roofline["traffic"] = tr.get("hbm_bytes_per_launch")
-            roofline["traffic_note"] = tr.get("note")
+            traffic_entries = json.load(f)
+        if isinstance(traffic_entries, dict):
+            traffic_entries = [traffic_entries]
     except (OSError, ValueError):
-        pass
+        traffic_entries = []
+
+    def roofline_of(name, g):
+        avg_ms = g["ms"] / g["launches"]
+        fl = g["flops"] / g["launches"]
+        r = {"kernel": name, "bound": "mfma", "achieved": fl / avg_ms / 1e9, "peak": PEAK_F16_TFLOPS,
+             "unit": "TFLOP/s", "frac": fl / avg_ms / 1e9 / PEAK_F16_TFLOPS, "traffic": None,
+             "avg_launch_us": avg_ms * 1e3, "launches_per_step": g["launches"], "ms_per_step": g["ms"],
+             "flop_per_launch": fl, "algorithmic_bytes_per_launch": g["bytes"] / g["launches"]}
+        for tr in traffic_entries:
+            if tr.get("kernel") == name:
+                r["traffic"] = tr.get("hbm_bytes_per_launch")
+                r["traffic_note"] = tr.get("note")
+        return r
+    ranked = sorted(((k, g) for k, g in groups.items() if single_kernel(k, g)), key=lambda kv: -kv[1]["ms"])
+    roofline = roofline_of(*ranked[0])
+    roofline["next_kernels"] = [roofline_of(k, g) for k, g in ranked[1:3]]
     unscale_gbs = 8.0 * dw_total / unscale_ms / 1e6
 
     # ---- side figures ---------------------------------------------------------------------------
