@@ -178,6 +178,23 @@ int conv2d_dgrad_fused(const conv2d_desc *desc, const void *dy, const void *w,
                        const conv2d_dgrad_epilogue *ep, void *dx, void *workspace,
                        size_t workspace_bytes, void *hip_stream);
 
+/* ---- callers that cannot allocate device memory ---------------------------------------------
+ * For code under HIP graph capture, tight serving loops and harnesses that forbid hipMalloc:
+ * conv2d_wgrad without a workspace argument.  The scratch conv2d_wgrad would take from its
+ * workspace (split-K partial sums, padded copies) lives in a device array of
+ * SDCONV_STATIC_SCRATCH_BYTES bytes inside the library, one copy per GPU, held until the process
+ * ends.  The call allocates and frees nothing and calls no allocating routine; its first call
+ * on a device looks the array's address up once (do that call outside a capture).
+ * Same arguments, results (bit for bit), alignment, ownership and asynchrony as conv2d_wgrad.
+ * SDCONV_EWORKSPACE when conv2d_workspace_bytes(desc, SDCONV_WGRAD) exceeds
+ * SDCONV_STATIC_SCRATCH_BYTES (nothing is enqueued); the other codes as conv2d_wgrad.
+ * All calls on one GPU share that GPU's array: calls that may overlap in time (different
+ * streams without an ordering between them, several host threads) race on it and give wrong
+ * results; order them on one stream or with events. */
+#define SDCONV_STATIC_SCRATCH_BYTES 67108864 /* 64 MiB */
+int conv2d_wgrad_static_scratch(const conv2d_desc *desc, const void *x, const void *dy, float *dw,
+                                void *hip_stream);
+
 /* ---- single-precision companion path ----------------------------------------------------------
  * Section 2.2 and Figure 1(b) of the paper compare mixed-precision training with full-precision
  * (FP32) training.  These calls run the same three passes on binary32 tensors (binary32

@@ -24,6 +24,7 @@ EXPORTS = (
     "sdconv_mfma_ceiling", "grad_unscale_check_dynamic", "sgd_momentum_update",
     "conv2d_fwd_fused", "conv2d_dgrad_fused", "sdconv_tail_pass",
     "conv2d_workspace_bytes_f32", "conv2d_fwd_f32", "conv2d_dgrad_f32", "conv2d_wgrad_f32",
+    "conv2d_wgrad_static_scratch",
 )
 
 
@@ -92,6 +93,8 @@ def lib() -> ctypes.CDLL:
             fn = getattr(L, name)
             fn.argtypes = [dp, vp, vp, vp, vp, sz, vp]
             fn.restype = ctypes.c_int
+        L.conv2d_wgrad_static_scratch.argtypes = [dp, vp, vp, vp, vp]
+        L.conv2d_wgrad_static_scratch.restype = ctypes.c_int
         L.sdconv_tail_pass.argtypes = [vp, sz, ctypes.c_int32, vp, vp, vp, vp, ctypes.c_int32, vp]
         L.sdconv_tail_pass.restype = ctypes.c_int
         L.sdconv_mfma_ceiling.argtypes = [vp, ctypes.c_int, ctypes.c_int, vp]
@@ -214,6 +217,16 @@ def sdconv_tail_pass(t, pixels: int, channels: int, stream: int = 0, *, scale=No
 
 def conv2d_wgrad(desc, x, dy, dw, workspace=None, stream: int = 0) -> None:
     _call("conv2d_wgrad", desc, x, dy, dw, workspace, stream)
+
+
+STATIC_SCRATCH_BYTES = 64 << 20
+
+
+def conv2d_wgrad_static_scratch(desc, x, dy, dw, stream: int = 0) -> None:
+    """conv2d_wgrad on the library's own fixed device scratch: allocates nothing."""
+    rc = lib().conv2d_wgrad_static_scratch(ctypes.byref(desc), _ptr(x), _ptr(dy), _ptr(dw), stream or 0)
+    if rc:
+        raise SdconvError(rc, "conv2d_wgrad_static_scratch")
 
 
 def grad_unscale_check_dynamic(grad, n: int, state, found_nonfinite, stream: int = 0) -> None:

@@ -145,6 +145,27 @@ extern "C" __attribute__((visibility("default"))) int conv2d_wgrad(const conv2d_
                                 (hipStream_t)hip_stream));
 }
 
+namespace sdconv {
+int wgrad_static_scratch(const Geom& g, const Plan& p, const __half* x, const __half* dy, float* dw, hipStream_t st,
+                         hipError_t* hip_error);
+}
+
+extern "C" __attribute__((visibility("default"))) int conv2d_wgrad_static_scratch(const conv2d_desc* desc, const void* x,
+                                                                                  const void* dy, float* dw,
+                                                                                  void* hip_stream)
+{
+    int Ho, Wo;
+    if (!desc_shape(desc, &Ho, &Wo)) return SDCONV_EINVAL;
+    Geom g = make_geom(*desc, Ho, Wo);
+    Plan p = plan_wgrad(g);
+    int rc = check_common(desc, x, dy, dw, nullptr, 0, 0, &Ho, &Wo);
+    if (rc) return rc;
+    hipError_t e = hipSuccess;
+    rc = wgrad_static_scratch(g, p, (const __half*)x, (const __half*)dy, dw, (hipStream_t)hip_stream, &e);
+    if (rc == SDCONV_EHIP) g_last_hip_error = (int)e;
+    return rc;
+}
+
 extern "C" __attribute__((visibility("default"))) size_t conv2d_workspace_bytes_f32(const conv2d_desc* desc, int pass)
 {
     int Ho, Wo;
