@@ -49,26 +49,50 @@ def frozen_bn_affine(gamma, beta, mean, var, eps):
     return scale, beta - mean * scale
 
 
-def conv2d_fwd_fused(d, x, w, scale=None, bias=None, residual=None, relu=False) -> np.ndarray:
-    """y[N,Ho,Wo,K] in fp64."""
+def _at(t: np.ndarray, idx):
+    """The whole tensor, or its flat elements idx."""
+    return t if idx is None else t.ravel()[np.asarray(idx, dtype=np.int64)]
+
+
+def fwd_tail(y, d, scale=None, bias=None, residual=None, relu=False, idx=None) -> np.ndarray:
+    """The elementwise part of the fused forward pass, applied to y = conv2d_fwd(d, x, w) in
+    fp64: y is the whole tensor [N,Ho,Wo,K], or its flat elements idx (then idx must be given,
+    so that the per-channel vectors and the shortcut are taken at the same positions)."""
     ho, wo = out_shape(d)
-    y = conv2d_fwd(d, x, w)
+    k = slice(None) if idx is None else np.asarray(idx, dtype=np.int64) % d.K
+    y = np.asarray(y, dtype=np.float64)
+    if idx is None and tuple(y.shape) != (d.N, ho, wo, d.K):
+        raise ValueError("y is the whole forward result")
     if scale is not None:
-        y = y * _vec(scale, d.K, "scale")[None, None, None, :]
+        y = y * _vec(scale, d.K, "scale")[k]
     if bias is not None:
-        y = y + _vec(bias, d.K, "bias")[None, None, None, :]
+        y = y + _vec(bias, d.K, "bias")[k]
     if residual is not None:
-        y = y + _act(residual, (d.N, ho, wo, d.K), "residual")
+        y = y + _at(_act(residual, (d.N, ho, wo, d.K), "residual"), idx)
     if relu:
         y = np.where(y > 0, y, 0.0)
     return y
 
 
-def conv2d_dgrad_fused(d, dy, w, scale=None, relu_mask=None) -> np.ndarray:
-    """dx[N,H,W,C] in fp64."""
-    dx = conv2d_dgrad(d, dy, w)
+def dgrad_tail(dx, d, scale=None, relu_mask=None, idx=None) -> np.ndarray:
+    """The elementwise part of the fused data gradient, applied to dx = conv2d_dgrad(d, dy, w)
+    in fp64 (whole tensor [N,H,W,C], or its flat elements idx)."""
+    c = slice(None) if idx is None else np.asarray(idx, dtype=np.int64) % d.C
+    dx = np.asarray(dx, dtype=np.float64)
+    if idx is None and tuple(dx.shape) != (d.N, d.H, d.W, d.C):
+        raise ValueError("dx is the whole data gradient")
     if scale is not None:
-        dx = dx * _vec(scale, d.C, "scale")[None, None, None, :]
+        dx = dx * _vec(scale, d.C, "scale")[c]
     if relu_mask is not None:
-        dx = np.where(_act(relu_mask, (d.N, d.H, d.W, d.C), "relu_mask") > 0, dx, 0.0)
+        dx = np.where(_at(_act(relu_mask, (d.N, d.H, d.W, d.C), "relu_mask"), idx) > 0, dx, 0.0)
     return dx
+
+
+def conv2d_fwd_fused(d, x, w, scale=None, bias=None, residual=None, relu=False, idx=None) -> np.ndarray:
+    """y[N,Ho,Wo,K] in fp64 (or the flat elements ``idx`` of it)."""
+    return fwd_tail(conv2d_fwd(d, x, w, idx=idx), d, scale, bias, residual, relu, idx)
+
+
+def conv2d_dgrad_fused(d, dy, w, scale=None, relu_mask=None, idx=None) -> np.ndarray:
+    """dx[N,H,W,C] in fp64 (or the flat elements ``idx`` of it)."""
+    return dgrad_tail(conv2d_dgrad(d, dy, w, idx=idx), d, scale, relu_mask, idx)

@@ -61,7 +61,9 @@ static double *widen(const uint16_t *src, size_t n)
 {
     double *dst = (double *)malloc((n ? n : 1) * sizeof(double));
     if (!dst) return NULL;
-    for (size_t i = 0; i < n; ++i) dst[i] = half_bits_to_double(src[i]);
+    /* independent elements: the loop is shared among the threads, nothing else changes */
+#pragma omp parallel for schedule(static)
+    for (long long i = 0; i < (long long)n; ++i) dst[i] = half_bits_to_double(src[i]);
     return dst;
 }
 
@@ -70,7 +72,8 @@ static double *widen_f32(const float *src, size_t n)
 {
     double *dst = (double *)malloc((n ? n : 1) * sizeof(double));
     if (!dst) return NULL;
-    for (size_t i = 0; i < n; ++i) dst[i] = (double)src[i];
+#pragma omp parallel for schedule(static)
+    for (long long i = 0; i < (long long)n; ++i) dst[i] = (double)src[i];
     return dst;
 }
 

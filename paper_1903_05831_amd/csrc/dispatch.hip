@@ -49,6 +49,18 @@ static const TunedEntry* tuned_lookup(const Geom& g, int pass)
     return nullptr;
 }
 
+// The LDS-DMA kernels address their binary16 operands with 32-bit BYTE offsets and use bit 31
+// of the offset as "outside the image / past the tile" (the hardware range check then writes
+// zeros).  A tensor of 2^30 elements or more has real data at such offsets, so a masked load
+// would fetch it instead of zeros: those layers take the register-staged kernels (igemm.hip,
+// wgrad.hip), which index elements and test every load themselves.
+static bool byte_offsets_fit_31_bits(const Geom& g)
+{
+    const long lim = 1L << 30;
+    return (long)g.N * g.H * g.W * g.C < lim && (long)g.N * g.Ho * g.Wo * g.K < lim &&
+           (long)g.K * g.R * g.S * g.C < lim;
+}
+
 // The MFMA route moves 16-byte (8-half) vectors along the channel axis of every tensor.
 static bool igemm_ok(const Geom& g)
 {
@@ -122,6 +134,7 @@ static int ws_variant_for(const Geom& g, bool dgrad, int v)
 
 static int pick_variant(const Geom& g, bool dgrad)
 {
+    if (!byte_offsets_fit_31_bits(g)) return (dgrad ? g.C : g.K) <= 64 ? 3 : 0;
     int fv = forced_variant();
     if (fv >= 400 && fv < 400 + kNumPatchVariants && patch_variant_ok(g, dgrad, fv)) return fv;
     if (fv >= 400) fv = -1;
@@ -211,7 +224,8 @@ Plan plan_dgrad(const Geom& g)
         return Plan{ROUTE_PADK, in.variant, 1, padk_filter_bytes(gp) + padk_act_bytes(gp) + in.workspace_bytes,
                     padk_name(in.name)};
     }
-    if (!force_direct() && g.C <= 4 && thin_dgrad_mfma_supported(g) && !env_int("SDCONV_NO_THIN_MFMA_DGRAD", 0))
+    if (!force_direct() && g.C <= 4 && thin_dgrad_mfma_supported(g) && byte_offsets_fit_31_bits(g) &&
+        !env_int("SDCONV_NO_THIN_MFMA_DGRAD", 0))
         return Plan{ROUTE_THIN, 1, 1, align256(thin_dgrad_mfma_workspace_bytes(g)), "thin_dgrad_mfma"};
     if (!force_direct() && g.C <= 4 && g.K % 8 == 0 && g.sh * g.sw <= kMaxClasses &&
         thin_dgrad_lds_bytes(g) <= 64 * 1024)
@@ -233,6 +247,7 @@ static const WgradVariant& wgrad_variant(int v)
 
 static int pick_wgrad_variant(const Geom& g)
 {
+    if (!byte_offsets_fit_31_bits(g)) return g.K <= 64 ? 1 : 0;
     int fv = forced_wgrad_variant();
     if ((fv >= 0 && fv < kNumWgradVariants) || (fv >= 100 && fv < 100 + kNumWgradDmaVariants)) return fv;
     if (const TunedEntry* e = tuned_lookup(g, SDCONV_WGRAD)) return e->variant;

@@ -220,3 +220,64 @@ def sample_indices(total: int, count: int, seed: int) -> np.ndarray:
     idx[0] = 0
     idx[-1] = total - 1
     return np.unique(idx).astype(np.int64)
+
+
+def stratified_indices(layer: ConvLayer, pass_id: int, seed: int, min_count: int = 100_000,
+                       row_window: int = 8) -> np.ndarray:
+    """Seeded flat output indices of one pass (0 forward: y, 1 data gradient: dx, 2 weight
+    gradient: dw) spread so that no tile of a kernel can be missed, whatever its shape:
+
+    y / dx: the pixels are listed per stride-parity class of the data gradient (one class for the
+    forward pass), in image order; of every `row_window` consecutive pixels of a list one is
+    drawn, plus the first and last pixel of the list; of every drawn pixel the first and last
+    channel and one channel out of each of `cpr` equal channel ranges are taken (cpr >= 4, raised
+    until min_count elements are reached); the first and last pixel of a list are taken whole.
+    dw: one element out of every (8 filters x tap x 8 channels) cell, plus uniform draws up to
+    min_count; tensors of up to 1.5 * min_count elements are taken whole."""
+    rng = np.random.default_rng(np.random.SeedSequence([BASE_SEED, 78, seed, pass_id]))
+    if pass_id == 2:
+        total = layer.K * layer.R * layer.S * layer.C
+        if total <= min_count * 3 // 2:
+            return np.arange(total, dtype=np.int64)
+        taps = layer.R * layer.S
+        kw, cw = (layer.K + 7) // 8, (layer.C + 7) // 8
+        k = np.minimum(np.arange(kw)[:, None, None] * 8 + rng.integers(0, 8, (kw, taps, cw)), layer.K - 1)
+        c = np.minimum(np.arange(cw)[None, None, :] * 8 + rng.integers(0, 8, (kw, taps, cw)), layer.C - 1)
+        t = np.arange(taps)[None, :, None]
+        idx = ((k * taps + t) * layer.C + c).ravel()
+        idx = np.unique(np.concatenate([idx, [0, total - 1]]))
+        while idx.size < min_count:
+            idx = np.unique(np.concatenate([idx, rng.integers(0, total, 2 * (min_count - idx.size))]))
+        return idx.astype(np.int64)
+    if pass_id == 0:
+        H, W, ncols, sh, sw = layer.Ho, layer.Wo, layer.K, 1, 1
+    else:
+        H, W, ncols, sh, sw = layer.H, layer.W, layer.C, layer.stride, layer.stride
+    if layer.N * H * W * ncols <= min_count * 3 // 2:
+        return np.arange(layer.N * H * W * ncols, dtype=np.int64)
+    lists = []
+    for a in range(sh):
+        for b in range(sw):
+            hh, ww = np.arange(a, H, sh), np.arange(b, W, sw)
+            if hh.size == 0 or ww.size == 0:
+                continue
+            pix = (np.arange(layer.N)[:, None, None] * H + hh[None, :, None]) * W + ww[None, None, :]
+            lists.append(pix.ravel())
+    nrows = sum((len(p) + row_window - 1) // row_window + 2 for p in lists)
+    cpr = int(min(ncols, max(4, -(-min_count // max(nrows, 1)))))
+    edges = np.linspace(0, ncols, cpr + 1).astype(np.int64)
+    out = []
+    for pix in lists:
+        m = len(pix)
+        nwin = (m + row_window - 1) // row_window
+        pos = np.minimum(np.arange(nwin) * row_window + rng.integers(0, row_window, nwin), m - 1)
+        pos = np.unique(np.concatenate([pos, [0, m - 1]]))
+        rows = pix[pos].astype(np.int64)
+        lo, hi = edges[:-1][None, :], edges[1:][None, :]
+        cols = lo + (rng.random((rows.size, cpr)) * (hi - lo)).astype(np.int64)
+        cols = np.concatenate([cols, np.zeros((rows.size, 1), np.int64),
+                               np.full((rows.size, 1), ncols - 1, np.int64)], axis=1)
+        out.append((rows[:, None] * ncols + cols).ravel())
+        for p in (pix[0], pix[-1]):
+            out.append(int(p) * ncols + np.arange(ncols, dtype=np.int64))
+    return np.unique(np.concatenate(out)).astype(np.int64)

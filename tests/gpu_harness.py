@@ -102,9 +102,10 @@ def compare(gpu: np.ndarray, ref: np.ndarray, what: str) -> None:
 PASS_NAMES = {sd.FWD: "fwd", sd.DGRAD: "dgrad", sd.WGRAD: "wgrad"}
 
 
-def check_all_passes(d, x: np.ndarray, w: np.ndarray, g: np.ndarray, tag: str, sample=None, seed=0):
+def check_all_passes(d, x: np.ndarray, w: np.ndarray, g: np.ndarray, tag: str, sample=None, seed=0, extra=None):
     """Runs fwd, dgrad, wgrad on the GPU and checks each against the oracle: the whole
-    tensor when `sample` is None, else `sample` seeded output elements per pass."""
+    tensor when `sample` is None, else `sample` seeded output elements per pass plus the flat
+    indices listed in extra[pass_id]."""
     from paper_1903_05831_amd import workloads
     od = oracle_desc(d)
     xd, wd, gd = to_dev(x), to_dev(w), to_dev(g)
@@ -121,6 +122,8 @@ def check_all_passes(d, x: np.ndarray, w: np.ndarray, g: np.ndarray, tag: str, s
             compare(got, ofn(od, a_np, b_np), what)
         else:
             idx = workloads.sample_indices(got.size, sample, seed + pass_id)
+            if extra and extra.get(pass_id):
+                idx = np.unique(np.concatenate([idx, np.asarray(extra[pass_id], dtype=idx.dtype)]))
             compare(got.ravel()[idx], ofn(od, a_np, b_np, idx=idx), what + f" ({idx.size} samples)")
 
 

@@ -136,3 +136,21 @@ def test_status_strings():
     for code in (sd.EINVAL, sd.EUNSUPPORTED, sd.EWORKSPACE, sd.EHIP, 99):
         assert isinstance(sd.status_string(code), str) and sd.status_string(code)
     assert sd.last_hip_error() == 0
+
+
+def test_tensors_of_2_30_elements_or_more_avoid_the_byte_offset_kernels():
+    """The LDS-DMA kernels use 32-bit byte offsets whose bit 31 marks a masked load (padding tap,
+    ragged row): 0x80000000 must not be the address of real data.  A binary16 tensor of 2^30
+    elements or more has data at byte 2^31 and beyond (host-side arithmetic below), so such layers
+    must be served by the kernels that index elements; smaller ones keep the LDS-DMA kernels."""
+    big = _desc(N=1, H=724, W=725, C=2048, K=8)
+    last_byte_offset = (big.N * big.H * big.W * big.C - 1) * 2
+    assert last_byte_offset >= 0x80000000          # a valid pixel would look like a masked one
+    for p in (sd.FWD, sd.DGRAD, sd.WGRAD):
+        name = sd.kernel_name(big, p)
+        assert "dma" not in name and "_ws_" not in name and "patch" not in name, name
+    small = _desc(N=1, H=724, W=724, C=2048, K=8)
+    assert (small.N * small.H * small.W * small.C - 1) * 2 < 0x80000000
+    assert any(t in sd.kernel_name(small, sd.FWD) for t in ("dma", "_ws_", "patch"))
+    # large y with a small x (many filters), and a large filter bank
+    assert "dma" not in sd.kernel_name(_desc(N=1, H=2048, W=2048, C=8, K=256, R=1, S=1, pad_h=0, pad_w=0), sd.WGRAD)

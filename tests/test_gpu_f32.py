@@ -1,9 +1,15 @@
 """GPU parity of the single-precision companion path (conv2d_*_f32) against the fp64 oracle on
 the same binary32 inputs.
 
-Tolerance: binary32 products and accumulation over n terms give a typical error of about
-sqrt(n) * 2^-24 * |ref| (n up to 4608 in the forward pass, 134400 in the weight gradient: below
-3e-5 relative); the bar is 2e-4 * (1 + |ref|) per element and 2e-5 in the Frobenius norm."""
+Tolerance: binary32 products are accumulated in binary32 in an order the kernel is free to
+choose.  A sum of n terms of rms size t that is accumulated one term after the other has partial
+sums of size sqrt(i) * t, each rounded with a relative error of up to 2^-24, so its error has an
+rms of about 2^-24 * n * t / sqrt(2) -- and it does not shrink when the terms cancel, so it cannot
+be bounded by a multiple of |ref|.  The bar per element is therefore
+    2e-4 * (1 + |ref|) + 2^-23 * n * t
+(n = contraction length of the pass: up to 4608 forward, 134 400 pixels in the weight gradient),
+and 2e-5 in the Frobenius norm.  Every comparison prints the largest |err| / bound it saw, and
+the largest |err| relative to the second term alone, so that the slack in the bar is visible."""
 import numpy as np
 import pytest
 import torch
@@ -26,12 +32,15 @@ def _compare(got, ref, what, nterms, term_rms):
     err = np.abs(g - r)
     bound = ELEM_TOL_F32 * (1 + np.abs(r)) + 2.0 ** -23 * nterms * term_rms
     worst = int(np.argmax(err - bound))
-    assert err[worst] <= bound[worst], f"{what}: element {worst} gpu={g[worst]!r} ref={r[worst]!r}"
     rn = np.linalg.norm(r)
-    assert np.linalg.norm(g - r) <= FRO_TOL_F32 * (rn if rn > 0 else 1.0), f"{what}: Frobenius"
+    fro = np.linalg.norm(g - r) / (rn if rn > 0 else 1.0)
+    say(f"    {what}: max err/bound {float(np.max(err / bound)):.3f}, max err / (2^-23 n t) "
+        f"{float(err.max() / (2.0 ** -23 * nterms * term_rms)):.3f}, Frobenius {fro:.2e} (bar {FRO_TOL_F32:.0e})")
+    assert err[worst] <= bound[worst], f"{what}: element {worst} gpu={g[worst]!r} ref={r[worst]!r}"
+    assert fro <= FRO_TOL_F32, f"{what}: Frobenius"
 
 
-def _check(d, x, w, g, tag, sample=None, seed=0):
+def _check(d, x, w, g, tag, sample=None, seed=0, layer=None):
     od = oracle_desc(d)
     ho, wo = sd.conv2d_out_shape(d)
     st = torch.cuda.current_stream().cuda_stream
@@ -54,8 +63,9 @@ def _check(d, x, w, g, tag, sample=None, seed=0):
         if sample is None:
             _compare(got, ofn(od, an, bn), what, nterms, term_rms)
         else:
-            idx = workloads.sample_indices(got.size, sample, seed + pid)
-            _compare(got.ravel()[idx], ofn(od, an, bn, idx=idx), what, nterms, term_rms)
+            idx = (workloads.stratified_indices(layer, pid, seed) if layer is not None
+                   else workloads.sample_indices(got.size, sample, seed + pid))
+            _compare(got.ravel()[idx], ofn(od, an, bn, idx=idx), what + f" ({idx.size} samples)", nterms, term_rms)
 
 
 def _rand32(N, H, W, C, K, R, S, stride, pad, dil, seed):
@@ -88,12 +98,29 @@ def test_f32_small_shapes_full_tensor(case):
     _check(d, x, w, g, f"f32{case}")
 
 
-@pytest.mark.parametrize("cfg,name", [(5, "res2.0a"), (5, "res3.0b"), (5, "res4.1b"), (5, "res5.1a"), (5, "res4.0p")])
-def test_f32_config_layers_sampled(cfg, name):
-    l = next(l for l in workloads.CONFIGS[cfg] if l.name == name)
-    say(f"f32 config layer {name} {l.x_shape}")
-    d, x, w, g = _rand32(l.N, l.H, l.W, l.C, l.K, l.R, l.S, (l.stride, l.stride), (l.pad, l.pad), (l.dil, l.dil), seed=11)
-    _check(d, x, w, g, f"f32.{name}", sample=2000, seed=3)
+def _distinct_backbone_and_head_shapes():
+    """First instance of every layer shape of the detector workload after the RGB stem (the
+    single-precision path takes channel counts in multiples of 4)."""
+    seen, out = set(), []
+    for li, l in enumerate(workloads.CONFIGS[5]):
+        key = (l.N, l.H, l.W, l.C, l.K, l.R, l.stride, l.pad)
+        if l.C % 4 or key in seen:
+            continue
+        seen.add(key)
+        out.append(li)
+    return out
+
+
+@pytest.mark.parametrize("li", _distinct_backbone_and_head_shapes(), ids=lambda v: workloads.CONFIGS[5][v].name)
+def test_f32_every_distinct_layer_shape_stratified_samples(li):
+    """Every distinct res2-res5 shape at full size, the launch bench.py times, on at least 1e5
+    stratified output elements per pass (workloads.stratified_indices)."""
+    l = workloads.CONFIGS[5][li]
+    say(f"f32 config layer {l.name} {l.x_shape} -> {l.y_shape}")
+    d, x, w, g = _rand32(l.N, l.H, l.W, l.C, l.K, l.R, l.S, (l.stride, l.stride), (l.pad, l.pad), (l.dil, l.dil),
+                         seed=1100 + li)
+    _check(d, x, w, g, f"f32.{l.name}", sample=True, seed=3, layer=l)
+    torch.cuda.empty_cache()
 
 
 def test_f32_unsupported_and_argument_checks():

@@ -28,6 +28,35 @@ def test_activation_tensor_just_below_2_31_elements():
     torch.cuda.empty_cache()
 
 
+def test_padded_3x3_on_a_tensor_of_more_than_2_30_elements():
+    """3x3, pad 1, 2048 -> 8 channels on one 724 x 725 image: x and dx hold 1 075 001 600 elements,
+    so their byte offsets pass 2^31 -- the value the LDS-DMA kernels use to mark a load as masked
+    (padding taps, ragged rows).  Such layers must take the kernels that index elements instead.
+    The samples include the image corners and pixels on both sides of the 2 GiB byte offset.
+    (Many channels rather than many pixels: the weight gradient then sums 524 900 pixels, as in the
+    detector workload, and binary32 accumulation stays inside the parity bar.)"""
+    l = workloads.ConvLayer("limit3x3", 1, 724, 725, 2048, 8, 3, 3, 1, 1, 724, 725)
+    assert 2 ** 30 < l.N * l.H * l.W * l.C < 2 ** 31
+    d = sd.desc_of(l)
+    for p in (sd.FWD, sd.DGRAD, sd.WGRAD):
+        name = sd.kernel_name(d, p)
+        assert "dma" not in name and "_ws_" not in name and "patch" not in name, name
+    say(f"limit layer {l.x_shape} -> {l.y_shape} 3x3 pad 1")
+    x, w, g = workloads.make_x(l, 9, 1), workloads.make_w(l, 9, 1), workloads.make_g(l, 9, 1)
+    # flat indices worth looking at: corners, last elements, both sides of byte offset 2^31
+    pix_2g = (2 ** 31 // 2) // l.C
+    extra_x = [0, l.C * (l.W - 1), l.C * l.W * (l.H - 1), l.C * (l.W * l.H - 1), l.C * l.W * l.H - 1] + \
+              [l.C * (pix_2g + o) + c for o in (-l.W - 1, -1, 0, 1, 300) for c in (0, l.C - 1)]
+    assert max(extra_x) < l.N * l.H * l.W * l.C
+    # y is small; its pixels next to the x pixels at the 2 GiB offset read across that offset
+    extra_y = [0, l.K * (l.Wo - 1), l.K * l.Wo * (l.Ho - 1), l.K * l.Wo * l.Ho - 1] + \
+              [l.K * (pix_2g + o) + k for o in (-l.Wo - 1, -1, 0, 1, 300) for k in (0, l.K - 1)]
+    check_all_passes(d, x, w, g, "limit3x3", sample=3000, seed=910,
+                     extra={sd.FWD: extra_y, sd.DGRAD: extra_x})
+    del x, w, g
+    torch.cuda.empty_cache()
+
+
 def test_unscale_more_than_2_31_elements():
     """n = 2^31 + 12345 fp32 gradients (8.6 GB), values from a seeded generator on the device
     (the host copy of each checked window is taken before the call and handed to the oracle):

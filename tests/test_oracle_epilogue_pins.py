@@ -163,3 +163,31 @@ def test_argument_checks():
         ep.conv2d_fwd_fused(d, x, w, scale=np.ones(d.C + 1, np.float32))  # wrong length
     with pytest.raises(TypeError):
         ep.conv2d_dgrad_fused(d, dy, w, relu_mask=np.ones((d.N, d.H, d.W, d.C), np.float32))
+
+
+def test_sampled_mode_picks_the_same_elements_and_channels():
+    """fwd_tail / dgrad_tail on flat elements idx must give what indexing the whole result gives:
+    the channel of a flat NHWC index is its remainder modulo the channel count (checked with
+    per-channel vectors that hold the channel number, whose effect can be read off the result)."""
+    d, x, w, dy, rng = _case(9, stride=(2, 2))
+    ho, wo = oracle.out_shape(d)
+    idx = np.array([0, 1, d.K - 1, d.K, 3 * d.K + 2, d.N * ho * wo * d.K - 1])
+    sc = rng.standard_normal(d.K).astype(np.float32)
+    bi = rng.standard_normal(d.K).astype(np.float32)
+    res = rng.standard_normal((d.N, ho, wo, d.K)).astype(np.float16)
+    full = ep.conv2d_fwd_fused(d, x, w, sc, bi, res, relu=True)
+    assert np.array_equal(ep.conv2d_fwd_fused(d, x, w, sc, bi, res, relu=True, idx=idx), full.ravel()[idx])
+    # bias = channel number on a zero convolution: the sampled result is the channel of each index
+    chan = np.arange(d.K, dtype=np.float32)
+    got = ep.fwd_tail(np.zeros(idx.size), d, bias=chan, idx=idx)
+    assert np.array_equal(got, [0, 1, d.K - 1, 0, 2, d.K - 1])
+    jdx = np.array([0, d.C - 1, d.C, 5 * d.C + 3, d.N * d.H * d.W * d.C - 1])
+    dsc = rng.standard_normal(d.C).astype(np.float32)
+    mask = np.maximum(rng.standard_normal((d.N, d.H, d.W, d.C)), 0).astype(np.float16)
+    fulld = ep.conv2d_dgrad_fused(d, dy, w, dsc, mask)
+    assert np.array_equal(ep.conv2d_dgrad_fused(d, dy, w, dsc, mask, idx=jdx), fulld.ravel()[jdx])
+    got = ep.dgrad_tail(np.ones(jdx.size), d, scale=np.arange(d.C, dtype=np.float32), idx=jdx)
+    assert np.array_equal(got, [0, d.C - 1, 0, 3, d.C - 1])
+    # the tails applied to a precomputed convolution are the fused calls
+    assert np.array_equal(ep.fwd_tail(oracle.conv2d_fwd(d, x, w), d, sc, bi, res, True), full)
+    assert np.array_equal(ep.dgrad_tail(oracle.conv2d_dgrad(d, dy, w), d, dsc, mask), fulld)
