@@ -24,11 +24,18 @@
  *     after the call.  Calls that share a workspace must be ordered on one stream.
  *   - Outputs are overwritten in full (beta = 0); dx positions that no filter tap
  *     reaches are written as +0.
- *   - Return value: SDCONV_OK or a negative SDCONV_E* code.  When an error is returned
- *     nothing has been enqueued.  No exception crosses this boundary.
+ *   - Return value: SDCONV_OK or a negative SDCONV_E* code.  SDCONV_EINVAL, SDCONV_EUNSUPPORTED
+ *     and SDCONV_EWORKSPACE are found before anything is enqueued.  SDCONV_EHIP reports a HIP
+ *     call that failed; a pass that takes several launches (a filter copy or padding kernel in
+ *     front of the main kernel, a reduction behind it) may then have enqueued the earlier ones,
+ *     and the output is undefined.  No exception crosses this boundary.
  *   - Every tensor must hold fewer than 2^31 elements (kernels use 32-bit offsets).
- *   - Thread safety: the library keeps no mutable global state except a per-thread
- *     record of the last HIP error; calls from several host threads are safe.
+ *   - Thread safety: calls from several host threads are safe.  The library's own state is a
+ *     per-thread record of the last HIP error, once-only kernel attribute settings, and small
+ *     device-side records that overlapping grad_unscale_check* calls take turns on (up to 1024
+ *     such calls may be in flight on one device at a time).
+ *   - Environment: none is read, unless SDCONV_TUNE=1 was set before the first call: then the
+ *     SDCONV_* variables of the tuner and of the variant tests override the kernel choice.
  */
 #ifndef SDCONV_H
 #define SDCONV_H
@@ -51,7 +58,7 @@ typedef struct {
 enum {
     SDCONV_OK = 0,
     SDCONV_EINVAL = -1,       /* null pointer, non-positive size, empty output, bad scale, misalignment */
-    SDCONV_EUNSUPPORTED = -2, /* the *_f32 calls only: C or K not a multiple of 4, more than 64 taps    */
+    SDCONV_EUNSUPPORTED = -2, /* reserved: every valid descriptor is served                             */
     SDCONV_EWORKSPACE = -3,   /* workspace missing or smaller than conv2d_workspace_bytes()             */
     SDCONV_EHIP = -4          /* a HIP call failed; see sdconv_last_hip_error()                         */
 };
@@ -154,6 +161,8 @@ typedef struct {
 
 /* y[n,ho,wo,k] = act( scale[k] * conv2d_fwd(x, w)[n,ho,wo,k] + bias[k] + residual[n,ho,wo,k] ),
  * every operation in binary32 on the binary32 accumulator, one rounding to binary16 at the end.
+ * (Exception: with a filter count K that is not a multiple of 8 and C that is, the convolution
+ * result is rounded to binary16 first and the tail is applied to that value: two roundings.)
  * `ep` itself is a HOST pointer and must not be NULL (all members NULL / 0 gives conv2d_fwd).
  * Workspace, alignment, ownership and error rules as conv2d_fwd; y must not overlap residual. */
 int conv2d_fwd_fused(const conv2d_desc *desc, const void *x, const void *w,
@@ -201,8 +210,9 @@ int conv2d_wgrad_static_scratch(const conv2d_desc *desc, const void *x, const vo
  * products and accumulation on the fp32 matrix instructions, results binary32), so that the
  * comparison can be made on this hardware; they are a measurement companion, not a tuned path.
  * Layouts, conventions, alignment, ownership, asynchrony and error rules are those of the
- * half-precision calls with every tensor binary32.  Supported: C and K multiples of 4, at most
- * 64 filter taps, stride_h * stride_w <= 16; other descriptors return SDCONV_EUNSUPPORTED. */
+ * half-precision calls with every tensor binary32.  C and K multiples of 4 with at most 64 filter
+ * taps and stride_h * stride_w <= 16 run on the matrix instructions; every other valid
+ * descriptor is served by one-thread-per-output kernels. */
 size_t conv2d_workspace_bytes_f32(const conv2d_desc *desc, int pass);
 int conv2d_fwd_f32(const conv2d_desc *desc, const float *x, const float *w, float *y,
                    void *workspace, size_t workspace_bytes, void *hip_stream);
@@ -220,27 +230,6 @@ int sdconv_last_hip_error(void);
 /* Name of the kernel variant the dispatcher picks for (desc, pass), e.g. for profiles.
  * Static string; "invalid" for a bad descriptor. */
 const char *sdconv_kernel_name(const conv2d_desc *desc, int pass);
-
-/* Measurement aid, not part of the convolution path: launches `blocks` workgroups of 8 waves
- * that each issue iters * 16 v_mfma_f32_32x32x16_f16 on registers only (32768 FLOP per
- * instruction and wave), i.e. blocks * 8 * iters * 16 * 32768 FLOP in total.  Timed by the
- * caller, it gives the fp16 matrix rate the device sustains (the clock under matrix load is
- * below the spec-sheet clock).  scratch: device buffer of at least blocks * 512 floats,
- * overwritten.  Asynchronous on hip_stream.  SDCONV_EINVAL for a null buffer or non-positive
- * counts. */
-int sdconv_mfma_ceiling(float *scratch, int blocks, int iters, void *hip_stream);
-
-/* Measurement aid: the elementwise tail of conv2d_fwd_fused / conv2d_dgrad_fused as a separate
- * in-place pass over t, a binary16 [pixels][channels] tensor (what runs after a convolution
- * when the tail is not fused; it reads and writes the whole activation once more, and rounds
- * to binary16 twice where the fused calls round once):
- *   v = t[p][c]; v *= scale[c]; v += bias[c]; v += residual[p][c]; relu: v = max(v, 0);
- *   relu_mask: v = relu_mask[p][c] > 0 ? v : 0;  t[p][c] = binary16(v)
- * with binary32 arithmetic; NULL pointers / relu == 0 leave a step out.  All pointers are
- * device pointers, 16-byte aligned; channels must be a multiple of 8.  Asynchronous on
- * hip_stream.  SDCONV_EINVAL for a null t, bad sizes or misalignment. */
-int sdconv_tail_pass(void *t, size_t pixels, int32_t channels, const float *scale, const float *bias,
-                     const void *residual, const void *relu_mask, int32_t relu, void *hip_stream);
 
 #ifdef __cplusplus
 }

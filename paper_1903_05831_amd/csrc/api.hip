@@ -1,5 +1,6 @@
 // C-ABI entry points of libsdconv: argument validation, kernel selection, launches.
 #include "common.h"
+#include "sdconv_bench.h"
 #include <math.h>
 
 using namespace sdconv;
@@ -179,7 +180,6 @@ static int f32_call(const conv2d_desc* desc, int pass, const float* a, const flo
     int Ho, Wo;
     if (!desc_shape(desc, &Ho, &Wo)) return SDCONV_EINVAL;
     Geom g = make_geom(*desc, Ho, Wo);
-    if (!f32_supported(g)) return SDCONV_EUNSUPPORTED;
     // 32-bit element offsets inside the kernels
     const size_t lim = (size_t)1 << 31;
     if ((size_t)g.N * g.H * g.W * g.C >= lim || (size_t)g.N * Ho * Wo * g.K >= lim) return SDCONV_EINVAL;

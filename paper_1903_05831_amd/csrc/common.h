@@ -3,6 +3,7 @@
 #include <hip/hip_runtime.h>
 #include <hip/hip_fp16.h>
 #include <stdint.h>
+#include <atomic>
 #include "sdconv.h"
 
 namespace sdconv {
@@ -59,6 +60,7 @@ struct Plan {
     int splits;              // wgrad: number of pixel-range partial sums
     size_t workspace_bytes;  // device scratch the pass needs
     const char* name;        // kernel variant name, static string
+    int steps_per_split = 0; // wgrad: 64-pixel steps each pixel range covers
 };
 Plan plan_fwd(const Geom& g);
 Plan plan_dgrad(const Geom& g);
@@ -69,7 +71,8 @@ hipError_t run_dgrad(const Geom& g, const Plan& p, const __half* dy, const __hal
                      const Epilogue& ep = no_epilogue());
 hipError_t run_wgrad(const Geom& g, const Plan& p, const __half* x, const __half* dy, float* dw, void* ws, hipStream_t st);
 
-// Single-precision companion path (conv_f32.hip): channel and filter counts in multiples of 4.
+// Single-precision companion path (conv_f32.hip): matrix kernels for channel and filter counts in
+// multiples of 4 (f32_supported), the direct kernels for everything else.
 bool f32_supported(const Geom& g);
 size_t f32_workspace_bytes(const Geom& g, int pass);
 hipError_t run_fwd_f32(const Geom& g, const float* x, const float* w, float* y, hipStream_t st);
@@ -82,6 +85,9 @@ hipError_t launch_direct_fwd(const Geom& g, const __half* x, const __half* w, __
 hipError_t launch_direct_dgrad(const Geom& g, const __half* dy, const __half* w, __half* dx, hipStream_t st,
                                const Epilogue& ep = no_epilogue());
 hipError_t launch_direct_wgrad(const Geom& g, const __half* x, const __half* dy, float* dw, hipStream_t st);
+hipError_t launch_direct_fwd_f32(const Geom& g, const float* x, const float* w, float* y, hipStream_t st);
+hipError_t launch_direct_dgrad_f32(const Geom& g, const float* dy, const float* w, float* dx, hipStream_t st);
+hipError_t launch_direct_wgrad_f32(const Geom& g, const float* x, const float* dy, float* dw, hipStream_t st);
 hipError_t launch_pad_channels(const __half* src, __half* dst, long rows, int K, int Kp, hipStream_t st);
 hipError_t launch_pad_rows(const __half* src, __half* dst, long n, long total, hipStream_t st);
 hipError_t launch_unpad_channels(const __half* yp, __half* y, long rows, int K, int Kp, const Epilogue& ep, hipStream_t st);

@@ -450,12 +450,12 @@ template <int MODE, int BM, int BN, int WGM, int WGN>
 static hipError_t launch_f32_variant(const F32Params& P, hipStream_t st)
 {
     constexpr size_t lds = 2 * (BM + BN) * kF32RowBytes + (3 * kMaxTaps + 4) * sizeof(int);
-    static bool configured = false;
-    if (!configured) {
+    static std::atomic<bool> configured{false};   // set once the attribute call has succeeded; a second thread may repeat it, harmlessly
+    if (!configured.load(std::memory_order_acquire)) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&igemm_f32_kernel<MODE, BM, BN, WGM, WGN>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         if (e != hipSuccess) return e;
-        configured = true;
+        configured.store(true, std::memory_order_release);
     }
     hipLaunchKernelGGL((igemm_f32_kernel<MODE, BM, BN, WGM, WGN>), dim3(P.total_tiles), dim3(256), lds, st, P);
     return hipGetLastError();
@@ -518,11 +518,13 @@ static hipError_t run_f32_igemm(const Geom& g, bool dgrad, const float* A, const
 
 hipError_t run_fwd_f32(const Geom& g, const float* x, const float* w, float* y, hipStream_t st)
 {
+    if (!f32_supported(g)) return launch_direct_fwd_f32(g, x, w, y, st);
     return run_f32_igemm(g, false, x, w, y, st);
 }
 
 hipError_t run_dgrad_f32(const Geom& g, const float* dy, const float* w, float* dx, void* ws, hipStream_t st)
 {
+    if (!f32_supported(g)) return launch_direct_dgrad_f32(g, dy, w, dx, st);
     float* wT = static_cast<float*>(ws);
     dim3 grid((g.C + 31) / 32, (g.K + 31) / 32, g.R * g.S);
     hipLaunchKernelGGL(filter_transpose_f32_kernel, grid, dim3(256), 0, st, w, wT, g.K, g.R * g.S, g.C);
@@ -535,12 +537,12 @@ template <int BM, int BN>
 static hipError_t launch_f32_wgrad(const F32WgradParams& P, hipStream_t st)
 {
     constexpr size_t lds = 2 * kF32BP * (BM + BN) * sizeof(float);
-    static bool configured = false;
-    if (!configured) {
+    static std::atomic<bool> configured{false};   // set once the attribute call has succeeded; a second thread may repeat it, harmlessly
+    if (!configured.load(std::memory_order_acquire)) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&wgrad_f32_kernel<BM, BN, 2, 2>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         if (e != hipSuccess) return e;
-        configured = true;
+        configured.store(true, std::memory_order_release);
     }
     long blocks = (long)P.tiles_c * P.tiles_k * P.R * P.S * P.splits;
     hipLaunchKernelGGL((wgrad_f32_kernel<BM, BN, 2, 2>), dim3((unsigned)blocks), dim3(256), lds, st, P);
@@ -549,6 +551,7 @@ static hipError_t launch_f32_wgrad(const F32WgradParams& P, hipStream_t st)
 
 hipError_t run_wgrad_f32(const Geom& g, const float* x, const float* dy, float* dw, void* ws, hipStream_t st)
 {
+    if (!f32_supported(g)) return launch_direct_wgrad_f32(g, x, dy, dw, st);
     F32WgradParams P;
     int bm, bn;
     f32_wgrad_shape(g, &bm, &bn, &P.splits, &P.steps_per_split);

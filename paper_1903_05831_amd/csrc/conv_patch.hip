@@ -276,13 +276,13 @@ static hipError_t launch_patch_variant_impl(const IgemmParams& P, hipStream_t st
     constexpr int NPL = ((TH + 2) * (TW + 2) + 8 * NI - 1) / (8 * NI);
     constexpr size_t lds = (size_t)NPB * NPL * NI * 1024 + (size_t)SB * TPS * BN * 128 + 2 * kMaxTaps * sizeof(int);
     static_assert(lds <= 160 * 1024, "LDS budget");
-    static bool configured = false;
-    if (!configured) {
+    static std::atomic<bool> configured{false};   // set once the attribute call has succeeded; a second thread may repeat it, harmlessly
+    if (!configured.load(std::memory_order_acquire)) {
         hipError_t e = hipFuncSetAttribute(
             reinterpret_cast<const void*>(&conv_patch_kernel<MODE, TH, TW, BN, WGM, WGN, SB, MF, NIW, TPS, NPB, NDW, TAIL>),
             hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         if (e != hipSuccess) return e;
-        configured = true;
+        configured.store(true, std::memory_order_release);
     }
     const int grid = ((P.total_tiles + 63) / 64) * 64;
     hipLaunchKernelGGL((conv_patch_kernel<MODE, TH, TW, BN, WGM, WGN, SB, MF, NIW, TPS, NPB, NDW, TAIL>), dim3(grid), dim3(64 * (WGM * WGN + NDW)),

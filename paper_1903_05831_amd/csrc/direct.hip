@@ -1,14 +1,22 @@
 // Direct (one result per thread / per block) convolution kernels.  They accept every
 // valid descriptor and are the route for channel counts the MFMA kernels do not tile
 // (C or K not a multiple of 8).  fp16 inputs, fp32 accumulation, the optional elementwise
-// tail in fp32, one rounding on store.
+// tail in fp32, one rounding on store.  The same kernels on fp32 tensors (T = float: fp32
+// products and sums, no tail) serve the descriptors the fp32 matrix kernels do not take.
 #include "common.h"
 
 namespace sdconv {
 
-__global__ __launch_bounds__(256) void direct_fwd_kernel(Geom g, const __half* __restrict__ x,
-                                                         const __half* __restrict__ w,
-                                                         __half* __restrict__ y, long total, Epilogue E)
+__device__ __forceinline__ float to_f32(__half v) { return __half2float(v); }
+__device__ __forceinline__ float to_f32(float v) { return v; }
+template <typename T> __device__ __forceinline__ T from_f32(float v);
+template <> __device__ __forceinline__ __half from_f32<__half>(float v) { return __float2half_rn(v); }
+template <> __device__ __forceinline__ float from_f32<float>(float v) { return v; }
+
+template <typename T>
+__global__ __launch_bounds__(256) void direct_fwd_kernel(Geom g, const T* __restrict__ x,
+                                                         const T* __restrict__ w,
+                                                         T* __restrict__ y, long total, Epilogue E)
 {
     long i = (long)blockIdx.x * blockDim.x + threadIdx.x;
     if (i >= total) return;
@@ -24,17 +32,18 @@ __global__ __launch_bounds__(256) void direct_fwd_kernel(Geom g, const __half* _
         for (int s = 0; s < g.S; ++s) {
             int wi = wo * g.sw - g.pw + s * g.dw;
             if (wi < 0 || wi >= g.W) continue;
-            const __half* xp = x + (((long)n * g.H + h) * g.W + wi) * g.C;
-            const __half* wp = w + (((long)k * g.R + r) * g.S + s) * g.C;
-            for (int c = 0; c < g.C; ++c) acc += __half2float(xp[c]) * __half2float(wp[c]);
+            const T* xp = x + (((long)n * g.H + h) * g.W + wi) * g.C;
+            const T* wp = w + (((long)k * g.R + r) * g.S + s) * g.C;
+            for (int c = 0; c < g.C; ++c) acc += to_f32(xp[c]) * to_f32(wp[c]);
         }
     }
-    y[i] = __float2half_rn(epilogue_apply(E, acc, k, i));
+    y[i] = from_f32<T>(epilogue_apply(E, acc, k, i));
 }
 
-__global__ __launch_bounds__(256) void direct_dgrad_kernel(Geom g, const __half* __restrict__ dy,
-                                                           const __half* __restrict__ w,
-                                                           __half* __restrict__ dx, long total, Epilogue E)
+template <typename T>
+__global__ __launch_bounds__(256) void direct_dgrad_kernel(Geom g, const T* __restrict__ dy,
+                                                           const T* __restrict__ w,
+                                                           T* __restrict__ dx, long total, Epilogue E)
 {
     long i = (long)blockIdx.x * blockDim.x + threadIdx.x;
     if (i >= total) return;
@@ -54,19 +63,20 @@ __global__ __launch_bounds__(256) void direct_dgrad_kernel(Geom g, const __half*
             if (tw < 0 || tw % g.sw) continue;
             int wo = tw / g.sw;
             if (wo >= g.Wo) continue;
-            const __half* gp = dy + (((long)n * g.Ho + ho) * g.Wo + wo) * g.K;
-            const __half* wp = w + ((long)r * g.S + s) * g.C + c;
+            const T* gp = dy + (((long)n * g.Ho + ho) * g.Wo + wo) * g.K;
+            const T* wp = w + ((long)r * g.S + s) * g.C + c;
             long wstride = (long)g.R * g.S * g.C;
-            for (int k = 0; k < g.K; ++k) acc += __half2float(gp[k]) * __half2float(wp[k * wstride]);
+            for (int k = 0; k < g.K; ++k) acc += to_f32(gp[k]) * to_f32(wp[k * wstride]);
         }
     }
-    dx[i] = __float2half_rn(epilogue_apply(E, acc, c, i));
+    dx[i] = from_f32<T>(epilogue_apply(E, acc, c, i));
 }
 
 // One workgroup per dw element: threads stride over output pixels, then a fixed-order
 // tree reduction (deterministic).
-__global__ __launch_bounds__(256) void direct_wgrad_kernel(Geom g, const __half* __restrict__ x,
-                                                           const __half* __restrict__ dy,
+template <typename T>
+__global__ __launch_bounds__(256) void direct_wgrad_kernel(Geom g, const T* __restrict__ x,
+                                                           const T* __restrict__ dy,
                                                            float* __restrict__ dw)
 {
     __shared__ float red[256];
@@ -86,8 +96,7 @@ __global__ __launch_bounds__(256) void direct_wgrad_kernel(Geom g, const __half*
         int h = ho * g.sh - g.ph + r * g.dh;
         int wi = wo * g.sw - g.pw + s * g.dw;
         if (h < 0 || h >= g.H || wi < 0 || wi >= g.W) continue;
-        acc += __half2float(dy[p * g.K + k]) *
-               __half2float(x[(((long)n * g.H + h) * g.W + wi) * g.C + c]);
+        acc += to_f32(dy[p * g.K + k]) * to_f32(x[(((long)n * g.H + h) * g.W + wi) * g.C + c]);
     }
     red[threadIdx.x] = acc;
     __syncthreads();
@@ -104,7 +113,7 @@ hipError_t launch_direct_fwd(const Geom& g, const __half* x, const __half* w, __
                              const Epilogue& ep)
 {
     long total = (long)g.N * g.Ho * g.Wo * g.K;
-    hipLaunchKernelGGL(direct_fwd_kernel, dim3(blocks_for(total)), dim3(256), 0, st, g, x, w, y, total, ep);
+    hipLaunchKernelGGL(direct_fwd_kernel<__half>, dim3(blocks_for(total)), dim3(256), 0, st, g, x, w, y, total, ep);
     return hipGetLastError();
 }
 
@@ -112,14 +121,39 @@ hipError_t launch_direct_dgrad(const Geom& g, const __half* dy, const __half* w,
                                const Epilogue& ep)
 {
     long total = (long)g.N * g.H * g.W * g.C;
-    hipLaunchKernelGGL(direct_dgrad_kernel, dim3(blocks_for(total)), dim3(256), 0, st, g, dy, w, dx, total, ep);
+    hipLaunchKernelGGL(direct_dgrad_kernel<__half>, dim3(blocks_for(total)), dim3(256), 0, st, g, dy, w, dx, total, ep);
     return hipGetLastError();
 }
 
 hipError_t launch_direct_wgrad(const Geom& g, const __half* x, const __half* dy, float* dw, hipStream_t st)
 {
     long total = (long)g.K * g.R * g.S * g.C;
-    hipLaunchKernelGGL(direct_wgrad_kernel, dim3((unsigned)total), dim3(256), 0, st, g, x, dy, dw);
+    hipLaunchKernelGGL(direct_wgrad_kernel<__half>, dim3((unsigned)total), dim3(256), 0, st, g, x, dy, dw);
+    return hipGetLastError();
+}
+
+// The single-precision companion path on descriptors its matrix kernels do not take (channel or
+// filter counts that are not a multiple of 4, more than 64 taps, more than 16 stride classes).
+hipError_t launch_direct_fwd_f32(const Geom& g, const float* x, const float* w, float* y, hipStream_t st)
+{
+    long total = (long)g.N * g.Ho * g.Wo * g.K;
+    hipLaunchKernelGGL(direct_fwd_kernel<float>, dim3(blocks_for(total)), dim3(256), 0, st, g, x, w, y, total,
+                       no_epilogue());
+    return hipGetLastError();
+}
+
+hipError_t launch_direct_dgrad_f32(const Geom& g, const float* dy, const float* w, float* dx, hipStream_t st)
+{
+    long total = (long)g.N * g.H * g.W * g.C;
+    hipLaunchKernelGGL(direct_dgrad_kernel<float>, dim3(blocks_for(total)), dim3(256), 0, st, g, dy, w, dx, total,
+                       no_epilogue());
+    return hipGetLastError();
+}
+
+hipError_t launch_direct_wgrad_f32(const Geom& g, const float* x, const float* dy, float* dw, hipStream_t st)
+{
+    long total = (long)g.K * g.R * g.S * g.C;
+    hipLaunchKernelGGL(direct_wgrad_kernel<float>, dim3((unsigned)total), dim3(256), 0, st, g, x, dy, dw);
     return hipGetLastError();
 }
 

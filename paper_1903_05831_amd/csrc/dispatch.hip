@@ -16,17 +16,20 @@ static int env_int(const char* name, int dflt)
     return (e && *e) ? atoi(e) : dflt;
 }
 
-static bool force_direct()
+// Tuning hooks (used by the tuner and by the tests that force every variant): environment
+// variables that override the dispatcher, honoured only when SDCONV_TUNE=1 was set before the
+// library's first call.  That switch is read once; without it no call touches the environment.
+static bool tuning()
 {
-    static int v = -1;
-    if (v < 0) v = env_int("SDCONV_FORCE_DIRECT", 0) ? 1 : 0;
-    return v == 1;
+    static const bool on = env_int("SDCONV_TUNE", 0) != 0;
+    return on;
 }
+static int hook(const char* name, int dflt) { return tuning() ? env_int(name, dflt) : dflt; }
 
-// Tuning hooks, read on every call so that a tuner can switch them between launches.
-static int forced_variant() { return env_int("SDCONV_IGEMM_VARIANT", -1); }
-static int forced_wgrad_splits() { return env_int("SDCONV_WGRAD_SPLITS", -1); }
-static int forced_wgrad_variant() { return env_int("SDCONV_WGRAD_VARIANT", -1); }
+static bool force_direct() { return hook("SDCONV_FORCE_DIRECT", 0) != 0; }
+static int forced_variant() { return hook("SDCONV_IGEMM_VARIANT", -1); }
+static int forced_wgrad_splits() { return hook("SDCONV_WGRAD_SPLITS", -1); }
+static int forced_wgrad_variant() { return hook("SDCONV_WGRAD_VARIANT", -1); }
 
 static size_t align256(size_t b) { return (b + 255) & ~(size_t)255; }
 
@@ -38,15 +41,25 @@ static const TunedEntry kTuned[] = {
     {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, -1, 0, 0},
 };
 
-static const TunedEntry* tuned_lookup(const Geom& g, int pass)
+// The table was measured at the batch sizes of the detector workloads.  A layer with the same
+// geometry and a batch within a factor of two of a measured one (half or twice the rows: the same
+// tile shapes still fill the chip about as well) takes that entry too, the exact batch first;
+// *scale_splits is then the factor by which the pixel count, and with it the number of pixel
+// ranges of a weight gradient, differs from the measured one.
+static const TunedEntry* tuned_lookup(const Geom& g, int pass, double* scale_splits = nullptr)
 {
-    if (env_int("SDCONV_NO_TUNED_TABLE", 0)) return nullptr;
-    for (const TunedEntry* e = kTuned; e->pass >= 0; ++e)
-        if (e->pass == pass && e->N == g.N && e->H == g.H && e->W == g.W && e->C == g.C && e->K == g.K &&
-            e->R == g.R && e->S == g.S && e->sh == g.sh && e->sw == g.sw && e->ph == g.ph && e->pw == g.pw &&
-            e->dh == g.dh && e->dw == g.dw)
-            return e;
-    return nullptr;
+    if (hook("SDCONV_NO_TUNED_TABLE", 0)) return nullptr;
+    const TunedEntry* near = nullptr;
+    for (const TunedEntry* e = kTuned; e->pass >= 0; ++e) {
+        if (!(e->pass == pass && e->H == g.H && e->W == g.W && e->C == g.C && e->K == g.K &&
+              e->R == g.R && e->S == g.S && e->sh == g.sh && e->sw == g.sw && e->ph == g.ph && e->pw == g.pw &&
+              e->dh == g.dh && e->dw == g.dw))
+            continue;
+        if (e->N == g.N) { near = e; break; }
+        if (!near && 2 * g.N >= e->N && g.N <= 2 * e->N) near = e;
+    }
+    if (near && scale_splits) *scale_splits = (double)g.N / near->N;
+    return near;
 }
 
 // The LDS-DMA kernels address their binary16 operands with 32-bit BYTE offsets and use bit 31
@@ -180,7 +193,7 @@ static bool thin_ok(const Geom& g) { return !force_direct() && g.C <= 4 && thin_
 // live in the workspace (padk.hip).
 static bool padk_ok(const Geom& g)
 {
-    if (force_direct() || env_int("SDCONV_NO_PADK", 0)) return false;
+    if (force_direct() || hook("SDCONV_NO_PADK", 0)) return false;
     if (g.K % 8 == 0 || g.C % 8 != 0 || g.R * g.S > kMaxTaps || g.sh * g.sw > kMaxClasses) return false;
     // the padded copies must stay below 2^31 elements like every other tensor
     const long kp = (g.K + 7) / 8 * 8, lim = 0x7fffffffL;
@@ -225,7 +238,7 @@ Plan plan_dgrad(const Geom& g)
                     padk_name(in.name)};
     }
     if (!force_direct() && g.C <= 4 && thin_dgrad_mfma_supported(g) && byte_offsets_fit_31_bits(g) &&
-        !env_int("SDCONV_NO_THIN_MFMA_DGRAD", 0))
+        !hook("SDCONV_NO_THIN_MFMA_DGRAD", 0))
         return Plan{ROUTE_THIN, 1, 1, align256(thin_dgrad_mfma_workspace_bytes(g)), "thin_dgrad_mfma"};
     if (!force_direct() && g.C <= 4 && g.K % 8 == 0 && g.sh * g.sw <= kMaxClasses &&
         thin_dgrad_lds_bytes(g) <= 64 * 1024)
@@ -269,7 +282,8 @@ static void wgrad_split(const Geom& g, int variant, int* splits, int* steps_per_
     long P = (long)g.N * g.Ho * g.Wo;
     long total_steps = (P + 63) / 64;
     long want = (384 + tiles - 1) / tiles;
-    if (const TunedEntry* e = tuned_lookup(g, SDCONV_WGRAD)) want = e->splits;
+    double scale = 1.0;
+    if (const TunedEntry* e = tuned_lookup(g, SDCONV_WGRAD, &scale)) want = (long)(e->splits * scale + 0.5);
     int fs = forced_wgrad_splits();
     if (fs > 0) want = fs;
     long cap = total_steps / 4;
@@ -295,7 +309,9 @@ Plan plan_wgrad(const Geom& g)
     int splits, sps;
     wgrad_split(g, v, &splits, &sps);
     size_t ws = splits > 1 ? align256((size_t)splits * g.K * g.R * g.S * g.C * sizeof(float)) : 0;
-    return Plan{ROUTE_IGEMM, v, splits, ws, wgrad_variant(v).name};
+    Plan p{ROUTE_IGEMM, v, splits, ws, wgrad_variant(v).name};
+    p.steps_per_split = sps;
+    return p;
 }
 
 static hipError_t run_igemm(const Geom& g, const Plan& p, bool dgrad, const __half* A, const __half* B,
@@ -410,7 +426,8 @@ hipError_t run_wgrad(const Geom& g, const Plan& p, const __half* x, const __half
     P.sh = g.sh; P.sw = g.sw; P.ph = g.ph; P.pw = g.pw; P.dh = g.dh; P.dw = g.dw;
     P.Ho = g.Ho; P.Wo = g.Wo;
     P.P = g.N * g.Ho * g.Wo;
-    wgrad_split(g, p.variant, &P.splits, &P.steps_per_split);
+    P.splits = p.splits;
+    P.steps_per_split = p.steps_per_split;
     P.tiles_k = (g.K + v.bm - 1) / v.bm;
     P.tiles_c = (g.C + v.bn - 1) / v.bn;
     P.out = (P.splits > 1) ? static_cast<float*>(ws) : dw;

@@ -258,12 +258,12 @@ template <int MODE, int BM, int BN, int WGM, int WGN>
 static hipError_t launch_variant(const IgemmParams& P, int total_tiles, hipStream_t st)
 {
     constexpr size_t lds = 2 * (BM + BN) * kRowBytes + (3 * kMaxTaps + 4) * sizeof(int);
-    static bool configured = false;
-    if (!configured) {
+    static std::atomic<bool> configured{false};   // set once the attribute call has succeeded; a second thread may repeat it, harmlessly
+    if (!configured.load(std::memory_order_acquire)) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&igemm_kernel<MODE, BM, BN, WGM, WGN>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         if (e != hipSuccess) return e;
-        configured = true;
+        configured.store(true, std::memory_order_release);
     }
     hipLaunchKernelGGL((igemm_kernel<MODE, BM, BN, WGM, WGN>), dim3(total_tiles), dim3(kThreads), lds, st, P);
     return hipGetLastError();

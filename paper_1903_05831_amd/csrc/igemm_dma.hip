@@ -244,13 +244,13 @@ static hipError_t launch_dma_variant_impl(const IgemmParams& P, hipStream_t st)
 {
     constexpr size_t lds = dma_lds_bytes<BM, BN, WGM, WGN, S, BK>();
     static_assert(lds <= 160 * 1024, "LDS budget");
-    static bool configured = false;
-    if (!configured) {
+    static std::atomic<bool> configured{false};   // set once the attribute call has succeeded; a second thread may repeat it, harmlessly
+    if (!configured.load(std::memory_order_acquire)) {
         hipError_t e = hipFuncSetAttribute(
             reinterpret_cast<const void*>(&igemm_dma_kernel<MODE, BM, BN, WGM, WGN, S, BK, TAIL>),
             hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         if (e != hipSuccess) return e;
-        configured = true;
+        configured.store(true, std::memory_order_release);
     }
     const int grid = ((P.total_tiles + 63) / 64) * 64;   // whole runs of 8 tiles on each of 8 XCDs
     hipLaunchKernelGGL((igemm_dma_kernel<MODE, BM, BN, WGM, WGN, S, BK, TAIL>), dim3(grid), dim3(64 * WGM * WGN), lds, st, P);

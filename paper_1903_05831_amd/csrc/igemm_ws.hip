@@ -364,13 +364,13 @@ static hipError_t launch_ws_mixed_impl(const IgemmParams& P0, hipStream_t st)
     constexpr size_t lds = (lds_big > lds_small ? lds_big : lds_small) + (4 * kMaxTaps + 4) * sizeof(int) + (size_t)BM * 12;
     static_assert(lds <= 160 * 1024, "LDS budget");
     if (P0.nclasses != 1) return hipErrorInvalidValue;
-    static bool configured = false;
-    if (!configured) {
+    static std::atomic<bool> configured{false};   // set once the attribute call has succeeded; a second thread may repeat it, harmlessly
+    if (!configured.load(std::memory_order_acquire)) {
         hipError_t e = hipFuncSetAttribute(
             reinterpret_cast<const void*>(&igemm_ws_mixed_kernel<MODE, BM, BN, BNS, WGM, WGN, S, SS, BK, MF, TAIL>),
             hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         if (e != hipSuccess) return e;
-        configured = true;
+        configured.store(true, std::memory_order_release);
     }
     // P0.tiles_n / P0.total_tiles describe the launch in BN-wide tiles.  Whole rounds of 256
     // workgroups stay BN wide (rounded down to whole row tiles); the rest is cut in two.
@@ -402,13 +402,13 @@ static hipError_t launch_ws_variant_impl(const IgemmParams& P, hipStream_t st)
 {
     constexpr size_t lds = (size_t)S * (BM + BN) * BK * 2 + (4 * kMaxTaps + 4) * sizeof(int) + (size_t)BM * 12;
     static_assert(lds <= 160 * 1024, "LDS budget");
-    static bool configured = false;
-    if (!configured) {
+    static std::atomic<bool> configured{false};   // set once the attribute call has succeeded; a second thread may repeat it, harmlessly
+    if (!configured.load(std::memory_order_acquire)) {
         hipError_t e = hipFuncSetAttribute(
             reinterpret_cast<const void*>(&igemm_ws_kernel<MODE, BM, BN, WGM, WGN, S, BK, NP, MF, TAIL>),
             hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         if (e != hipSuccess) return e;
-        configured = true;
+        configured.store(true, std::memory_order_release);
     }
     const int grid = ((P.total_tiles + 63) / 64) * 64;   // whole runs of 8 tiles on each of 8 XCDs
     hipLaunchKernelGGL((igemm_ws_kernel<MODE, BM, BN, WGM, WGN, S, BK, NP, MF, TAIL>), dim3(grid),

@@ -558,12 +558,12 @@ hipError_t launch_thin_fwd(const Geom& g, const __half* x, const __half* w, __ha
     P.X = x; P.Wp = wp; P.Y = y;
     P.ep = ep;
     size_t lds = (size_t)g.R * 4 * kKT * 16 + (((size_t)P.PH * P.PW * 8 + 15) & ~(size_t)15) + 256 * 128;
-    static bool configured = false;
-    if (!configured) {
+    static std::atomic<bool> configured{false};   // set once the attribute call has succeeded; a second thread may repeat it, harmlessly
+    if (!configured.load(std::memory_order_acquire)) {
         e = hipFuncSetAttribute(reinterpret_cast<const void*>(&thin_fwd_kernel),
                                 hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
         if (e != hipSuccess) return e;
-        configured = true;
+        configured.store(true, std::memory_order_release);
     }
     const int grid = balanced_grid(P.ntiles, 512);     // two workgroups per compute unit fit in LDS
     hipLaunchKernelGGL(thin_fwd_kernel, dim3(grid, ktiles), dim3(256), lds, st, P);
@@ -578,12 +578,12 @@ hipError_t launch_thin_wgrad(const Geom& g, const __half* x, const __half* dy, f
     P.X = x; P.G = dy; P.partial = static_cast<float*>(ws);
     size_t lds = (size_t)kTH * kTW * kKT * 2 + (size_t)P.PH * P.PW * 8;
     hipError_t e;
-    static bool configured = false;
-    if (!configured) {
+    static std::atomic<bool> configured{false};   // set once the attribute call has succeeded; a second thread may repeat it, harmlessly
+    if (!configured.load(std::memory_order_acquire)) {
         e = hipFuncSetAttribute(reinterpret_cast<const void*>(&thin_wgrad_kernel),
                                 hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
         if (e != hipSuccess) return e;
-        configured = true;
+        configured.store(true, std::memory_order_release);
     }
     hipLaunchKernelGGL(thin_wgrad_kernel, dim3(nwg, ktiles), dim3(256), lds, st, P);
     e = hipGetLastError();

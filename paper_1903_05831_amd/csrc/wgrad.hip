@@ -230,12 +230,12 @@ template <int BM, int BN, int WGM, int WGN>
 static hipError_t launch_wvariant(const WgradParams& P, hipStream_t st)
 {
     constexpr size_t lds = 2 * kBP * (BM + BN) * 2;
-    static bool configured = false;
-    if (!configured) {
+    static std::atomic<bool> configured{false};   // set once the attribute call has succeeded; a second thread may repeat it, harmlessly
+    if (!configured.load(std::memory_order_acquire)) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&wgrad_kernel<BM, BN, WGM, WGN>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         if (e != hipSuccess) return e;
-        configured = true;
+        configured.store(true, std::memory_order_release);
     }
     long blocks = (long)P.tiles_c * P.tiles_k * P.R * P.S * P.splits;
     hipLaunchKernelGGL((wgrad_kernel<BM, BN, WGM, WGN>), dim3((unsigned)blocks), dim3(kWThreads), lds, st, P);

@@ -253,8 +253,8 @@ static hipError_t launch_wdma(const WgradParams& P0, hipStream_t st)
     constexpr size_t lds = (size_t)S * BP * (BM + BN) * 2 + (size_t)S * BP * sizeof(unsigned);
     static_assert(lds <= 160 * 1024, "LDS budget");
     const bool linear = P0.R == 1 && P0.S == 1 && P0.sh == 1 && P0.sw == 1 && P0.ph == 0 && P0.pw == 0;
-    static bool configured = false;
-    if (!configured) {
+    static std::atomic<bool> configured{false};   // set once the attribute call has succeeded; a second thread may repeat it, harmlessly
+    if (!configured.load(std::memory_order_acquire)) {
         hipError_t e = hipFuncSetAttribute(
             reinterpret_cast<const void*>(&wgrad_dma_kernel<BM, BN, WGM, WGN, S, BP, false, HF, MF>),
             hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
@@ -263,7 +263,7 @@ static hipError_t launch_wdma(const WgradParams& P0, hipStream_t st)
             reinterpret_cast<const void*>(&wgrad_dma_kernel<BM, BN, WGM, WGN, S, BP, true, HF, MF>),
             hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         if (e != hipSuccess) return e;
-        configured = true;
+        configured.store(true, std::memory_order_release);
     }
     WgradParams P = P0;
     P.total_blocks = P.tiles_c * P.tiles_k * P.R * P.S * P.splits;

@@ -3,8 +3,9 @@ GPU at hand and writes the winners to csrc/tuned_table.inc (rebuild the library 
 
     python -m paper_1903_05831_amd.tune [--configs 5] [--ms 10]
 
-The dispatcher reads SDCONV_IGEMM_VARIANT / SDCONV_WGRAD_SPLITS on every call, which is how
-this script forces a variant.  Unlisted geometries keep using the built-in heuristics.
+With SDCONV_TUNE=1 in the environment before the library's first call (set below) the dispatcher
+reads SDCONV_IGEMM_VARIANT / SDCONV_WGRAD_VARIANT / SDCONV_WGRAD_SPLITS on every call, which is
+how this script forces a variant.  Unlisted geometries keep using the built-in heuristics.
 
 In a training step every layer finds its inputs in HBM, not in the 256 MB Infinity Cache: the
 timed calls therefore rotate over enough copies of the layer's tensors (--cold-mib of
@@ -19,6 +20,8 @@ import os
 import sys
 
 import torch
+
+os.environ["SDCONV_TUNE"] = "1"      # before the first library call: enables the override hooks
 
 import paper_1903_05831_amd as sd
 from paper_1903_05831_amd import workloads

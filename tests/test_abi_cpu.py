@@ -14,7 +14,7 @@ ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
 
 def test_library_exports_every_declared_symbol():
-    header = open(os.path.join(ROOT, "include", "sdconv.h")).read()
+    header = "".join(open(os.path.join(ROOT, "include", h)).read() for h in ("sdconv.h", "sdconv_bench.h"))
     header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
     declared = set(re.findall(r"\b(\w+)\s*\(", header)) - {"defined"}
     assert declared == set(sd.EXPORTS)
@@ -154,3 +154,21 @@ def test_tensors_of_2_30_elements_or_more_avoid_the_byte_offset_kernels():
     assert any(t in sd.kernel_name(small, sd.FWD) for t in ("dma", "_ws_", "patch"))
     # large y with a small x (many filters), and a large filter bank
     assert "dma" not in sd.kernel_name(_desc(N=1, H=2048, W=2048, C=8, K=256, R=1, S=1, pad_h=0, pad_w=0), sd.WGRAD)
+
+
+def test_neighbouring_batch_sizes_take_the_tuned_entries():
+    """The measured table holds the layers of the workloads at their batch sizes; the same geometry
+    at half or twice the batch takes the same kernel variant, four times the batch does not."""
+    import dataclasses
+    hits = 0
+    for l in workloads.CONFIGS[5][1:40]:
+        base = [sd.kernel_name(sd.desc_of(l), p) for p in (sd.FWD, sd.DGRAD, sd.WGRAD)]
+        for n in (1, 4):
+            other = [sd.kernel_name(sd.desc_of(dataclasses.replace(l, N=n)), p) for p in (sd.FWD, sd.DGRAD, sd.WGRAD)]
+            assert other == base, (l.name, n, base, other)
+            hits += 1
+    assert hits == 78
+    # the pixel ranges of the weight gradient follow the batch
+    l = next(l for l in workloads.CONFIGS[5] if l.name == "res4.1b")
+    ws = [sd.conv2d_workspace_bytes(sd.desc_of(dataclasses.replace(l, N=n)), sd.WGRAD) for n in (1, 2, 4)]
+    assert ws[0] < ws[1] < ws[2]

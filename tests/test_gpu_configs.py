@@ -175,6 +175,30 @@ def test_second_shape_set_stratified_samples_plain_and_fused(cfg, li):
     _sampled(cfg, li, fused=True)
 
 
+@pytest.mark.parametrize("batch", [1, 4])
+@pytest.mark.parametrize("name", ["res2.0c", "res3.0b", "res3.1b", "res4.1a", "res4.1b", "res4.0p"])
+def test_other_batch_sizes(name, batch):
+    """The tuned table was measured at N = 2; N = 1 and N = 4 take the same entries (tile variant,
+    pixel ranges of the weight gradient scaled with the batch): stratified samples, all passes."""
+    import dataclasses
+    li, l2 = next((i, l) for i, l in enumerate(workloads.CONFIGS[5]) if l.name == name)
+    l = dataclasses.replace(l2, N=batch)
+    d = sd.desc_of(l)
+    assert sd.kernel_name(d, sd.FWD) == sd.kernel_name(sd.desc_of(l2), sd.FWD)
+    say(f"{name} at N={batch}: " + ", ".join(sd.kernel_name(d, p) for p in (sd.FWD, sd.DGRAD, sd.WGRAD)))
+    cfg = 70 + batch
+    x, w, g = workloads.make_x(l, cfg, li), workloads.make_w(l, cfg, li), workloads.make_g(l, cfg, li)
+    od = oracle_desc(d)
+    xd, wd, gd = to_dev(x), to_dev(w), to_dev(g)
+    for p, a, b, ofn, an, bn in ((sd.FWD, xd, wd, oracle.conv2d_fwd, x, w), (sd.DGRAD, gd, wd, oracle.conv2d_dgrad, g, w),
+                                 (sd.WGRAD, xd, gd, oracle.conv2d_wgrad, x, g)):
+        out = run_pass(d, p, a, b)
+        assert out.all_written()
+        idx = workloads.stratified_indices(l, p, cfg * 100 + li, min_count=50_000)
+        compare(out.numpy().ravel()[idx], ofn(od, an, bn, idx=idx), f"{name} N={batch} {PASS_NAMES[p]}")
+    torch.cuda.empty_cache()
+
+
 def test_dgrad_zero_fill_and_determinism_res3_projection():
     """1x1 stride-2 projection (256->512 from 200x336): dx is +0 at every pixel no tap reaches,
     and two runs give identical bits for all three passes."""

@@ -123,12 +123,25 @@ def test_f32_every_distinct_layer_shape_stratified_samples(li):
     torch.cuda.empty_cache()
 
 
-def test_f32_unsupported_and_argument_checks():
-    d = sd.make_desc(1, 8, 8, 3, 8, 3, 3, (1, 1), (1, 1), (1, 1))          # C = 3
+ODD = [
+    (1, 9, 11, 3, 5, 3, 3, (1, 1), (1, 1), (1, 1)),          # channel / filter counts the matrix kernels do not take
+    (2, 7, 8, 6, 4, 3, 3, (2, 2), (1, 1), (1, 1)),           # C = 6, strided
+    (1, 12, 12, 4, 4, 9, 9, (1, 1), (4, 4), (1, 1)),         # 81 taps
+    (1, 21, 23, 4, 4, 3, 3, (5, 5), (1, 1), (1, 1)),         # 25 stride classes
+]
+
+
+@pytest.mark.parametrize("case", ODD, ids=lambda c: "x".join(str(v) for v in c[:7]))
+def test_f32_descriptors_outside_the_matrix_kernels(case):
+    """Every valid descriptor is served: these take the one-thread-per-output kernels."""
+    say(f"f32 direct case {case}")
+    d, x, w, g = _rand32(*case, seed=sum(case[:7]) + 7)
+    assert all(sd.conv2d_workspace_bytes_f32(d, p) == 0 for p in (sd.FWD, sd.DGRAD, sd.WGRAD))
+    _check(d, x, w, g, f"f32direct{case}")
+
+
+def test_f32_argument_checks():
     t = torch.zeros(4096, dtype=torch.float32, device="cuda")
-    with pytest.raises(sd.SdconvError) as e:
-        sd.conv2d_fwd_f32(d, t, t, t, None, 0)
-    assert e.value.status == -2
     d = sd.make_desc(1, 8, 8, 8, 8, 3, 3, (1, 1), (1, 1), (1, 1))
     assert sd.conv2d_workspace_bytes_f32(d, sd.DGRAD) > 0
     with pytest.raises(sd.SdconvError) as e:
