@@ -84,7 +84,9 @@ __device__ __forceinline__ void store_rows_via_lds(Acc (&acc)[FN][FM], unsigned 
                 if (RPI <= MF || r < MF) {              // (there may be more lanes than strip chunks)
                     h8 v = *reinterpret_cast<const h8*>(strip + r * PITCH + schunk * 16);
                     const long pix = pix_of(b * MF + r);
-                    if (pix >= 0 && col < P.Cd) *reinterpret_cast<h8*>(P.D + pix * P.Cd + col) = v;
+                    // streaming store: the result is not read again by this kernel, and keeping it out
+                    // of the way of the operand lines in L2 is worth 1.6 % of the detector step
+                    if (pix >= 0 && col < P.Cd) __builtin_nontemporal_store(v, reinterpret_cast<h8*>(P.D + pix * P.Cd + col));
                 }
             }
             strip_handover();
@@ -165,7 +167,7 @@ __device__ __forceinline__ void store_rows_via_lds(Acc (&acc)[FN][FM], unsigned 
             h8 o;
 #pragma unroll
             for (int e = 0; e < 8; ++e) o[e] = (_Float16)v[e];
-            *reinterpret_cast<h8*>(P.D + off[b][j]) = o;
+            __builtin_nontemporal_store(o, reinterpret_cast<h8*>(P.D + off[b][j]));
         }
         strip_handover();
     }

@@ -226,7 +226,7 @@ __global__ __launch_bounds__(256) void thin_fwd_kernel(ThinParams P)
             int k = kt * kKT + part * 8;
             if (ho < P.Ho && wo < P.Wo && k < P.K) {
                 uint4v v = *reinterpret_cast<const uint4v*>(stage + pix * 128 + ((part ^ (pix & 7)) << 4));
-                *reinterpret_cast<uint4v*>(P.Y + ((((long)n * P.Ho + ho) * P.Wo + wo) * P.K + k)) = v;
+                __builtin_nontemporal_store(v, reinterpret_cast<uint4v*>(P.Y + ((((long)n * P.Ho + ho) * P.Wo + wo) * P.K + k)));
             }
         }
     }
