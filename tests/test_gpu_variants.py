@@ -80,6 +80,8 @@ WS_SHAPES = [
     (2, 23, 29, 64, 72, 3, 3, (2, 2), (1, 1), (1, 1)),      # strided: parity classes in the data gradient
     (1, 31, 37, 136, 200, 3, 3, (1, 1), (1, 1), (1, 1)),    # short last channel slab, filter tail
     (1, 31, 37, 128, 264, 1, 1, (1, 1), (0, 0), (1, 1)),    # 1x1, more than one 256-wide column tile
+    (2, 23, 29, 72, 64, 1, 1, (2, 2), (0, 0), (1, 1)),      # 1x1 stride 2, odd image: three parity classes of the data gradient are all zeros
+    (1, 21, 27, 64, 64, 1, 3, (2, 2), (0, 1), (1, 1)),      # 1x3 stride 2: the odd-row classes have no taps, both even-row classes do
 ]
 WS_VARIANTS = list(range(300, 325))
 
