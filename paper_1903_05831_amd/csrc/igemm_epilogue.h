@@ -174,6 +174,30 @@ __device__ __forceinline__ void store_rows_via_lds(Acc (&acc)[FN][FM], unsigned 
     }
 }
 
+// A data-gradient tile of a stride-parity class that no filter tap reaches is all zeros: written
+// directly, 16 bytes per lane on consecutive chunks of a pixel row, without tables or strips.
+// Rows m_base .. m_base + WM - 1 and columns col_base .. col_base + WN - 1 of the class's GEMM.
+template <int WM, int WN>
+__device__ __forceinline__ void store_zero_subtile(int lane, int m_base, int col_base, int Mcls, const IgemmParams& P,
+                                                   int Hi, int Wj, int eh, int ew, int ca, int cb)
+{
+    typedef _Float16 h8 __attribute__((ext_vector_type(8)));
+    constexpr int CW = WN / 8, RPI = 64 / CW;      // lanes per row, rows per store instruction
+    static_assert(64 % CW == 0, "whole rows per instruction");
+    const int srow = lane / CW, col = col_base + (lane % CW) * 8;
+    const h8 z = {0, 0, 0, 0, 0, 0, 0, 0};
+    if (col >= P.Cd) return;
+    for (int r = srow; r < WM; r += RPI) {
+        const int m = m_base + r;
+        if (m >= Mcls) break;
+        const int n = m / (Hi * Wj);
+        const int rem = m - n * (Hi * Wj);
+        const int i = rem / Wj, jj = rem - i * Wj;
+        const long pix = ((long)n * P.Hd + (i * eh + ca)) * P.Wd + (jj * ew + cb);
+        __builtin_nontemporal_store(z, reinterpret_cast<h8*>(P.D + pix * P.Cd + col));
+    }
+}
+
 // Rows are GEMM rows m_base.. of an implicit-GEMM tile (pixels of one stride-parity class in
 // (n, i, j) order; eh/ew/ca/cb place class pixel (i, j) at (i*eh + ca, j*ew + cb)).
 template <int FM, int FN, int MF = 32, bool TAIL = false, typename Acc>

@@ -118,6 +118,12 @@ __device__ __forceinline__ void igemm_ws_body(const IgemmParams& P, const int ti
     }
     __syncthreads();
     const int ntaps = __builtin_amdgcn_readfirstlane(tap_cnt[0]);
+    if (MODE == 1 && !TAIL && ntaps == 0) {
+        // a class without taps (three of the four of a 1x1 stride-2 layer): nothing to multiply
+        if (wave < NWC)
+            store_zero_subtile<WM, WN>(lane, m0 + (wave / WGN) * WM, n0 + (wave % WGN) * WN, Mcls, P, Hi, Wj, eh, ew, ca, cb);
+        return;
+    }
     const int kchunks = (P.Cs + BK - 1) / BK;
     const int nk = ntaps * kchunks;
 
